@@ -1,0 +1,364 @@
+"""Pins for the CPU oracle: every check here rests on something other than the oracle itself --
+the values Table 1 prints, hand-worked examples, closed forms evaluated in numpy float64,
+exhaustive invariants, brute force over the tiny parameter space, and double-precision tanh.
+No GPU is touched.
+"""
+import numpy as np
+import pytest
+
+from conftest import read_golden
+from paper_1909_07729_amd import workloads as wl
+
+
+def _table1_from_text():
+    """Table 1 from the text fixture -> list of (E, r, b) by integer index t."""
+    rows = read_golden("table1_bf16.txt")
+    assert len(rows) == 32
+    tab = [None] * 32
+    for bits, E, r, b in rows:
+        t = int(bits, 2)
+        assert tab[t] is None, "index printed twice"
+        tab[t] = (int(E), int(r), int(b))
+    return tab
+
+
+def _bf16_val(bits):
+    return wl.bf16_bits_to_f32(np.asarray(bits, dtype=np.uint16)).astype(np.float64)
+
+
+def _f32_val(bits):
+    return np.asarray(bits, dtype=np.uint32).view(np.float32).astype(np.float64)
+
+
+# ---------------------------------------------------------------- the table and its fit
+def test_table1_constants_match_the_paper(oracle):
+    assert oracle.table1().as_tuples() == _table1_from_text()
+
+
+def test_fit_regenerates_table1(oracle):
+    """Section 2.4 Steps 1-3 must give back all 32 printed triples."""
+    assert oracle.fit_lut().as_tuples() == _table1_from_text()
+
+
+def test_table1_is_the_brute_force_argmin_of_eq1():
+    """Independent of the C fit: enumerate every (r, b) in range and score eq. (1) in numpy."""
+    tab = _table1_from_text()
+    p, s = 7, 3
+    for t in range(32):
+        e_in = {1: 125, 2: 126, 3: 127, 0: 128}[t >> 3]
+        j = t & 7
+        m = np.arange(j * 16, j * 16 + 16, dtype=np.float64)
+        y = np.tanh(np.ldexp(1.0 + m / 128.0, e_in - 127))
+        fr, ex = np.frexp(y)
+        Ei = ex - 1 + 127
+        Mi = (2.0 * fr - 1.0) * 128.0
+        # Step 2
+        best = None
+        for E in sorted(set(Ei.tolist())):
+            Mh = np.where(Ei == E, Mi, np.where(E > Ei, 0.0, 127.0))
+            cost = np.sum((y - np.ldexp(1.0 + Mh / 128.0, E - 127)) ** 2)
+            if best is None or cost < best[0]:
+                best = (cost, E, Mh)
+        _, E, Mh = best
+        # Step 3 by exhaustive search under the b_min / b_max bounds
+        arg, arg_cost = None, np.inf
+        for r in range(0, p + 1):
+            bmax = 2 ** p - 1 - (((j + 1) * 2 ** (p - s) - 1) >> r)
+            bmin = -j * (2 ** (p - s - r) if p - s - r >= 0 else 0)
+            for b in range(bmin, bmax + 1):
+                cost = np.sum((Mh - (m / 2.0 ** r + b)) ** 2)
+                if cost < arg_cost:
+                    arg, arg_cost = (r, b), cost
+        assert (E, arg[0], arg[1]) == tab[t], f"interval {t:05b}"
+
+
+def test_table1_respects_overflow_bounds():
+    """(M >> r) + b stays inside [0, 127] over each interval (the purpose of b_min, b_max)."""
+    for t, (E, r, b) in enumerate(_table1_from_text()):
+        j = t & 7
+        lo, hi = (j * 16 >> r) + b, ((j * 16 + 15) >> r) + b
+        assert 0 <= lo <= hi <= 127 and 1 <= E <= 254 and 0 <= r <= 7
+
+
+# ---------------------------------------------------------------- Algorithm 1, BFloat16
+def test_worked_values(oracle):
+    for fmt, xin, xout, *_ in read_golden("worked_values.txt"):
+        if fmt == "bf16":
+            got = oracle.ktanh_bf16(np.array([int(xin, 16)], dtype=np.uint16))[0]
+        else:
+            got = oracle.ktanh_f32(np.array([int(xin, 16)], dtype=np.uint32))[0]
+        assert int(got) == int(xout, 16), f"{fmt} {xin}: got {int(got):X}, expected {xout}"
+
+
+def test_bf16_closed_form_on_the_table_region(oracle):
+    """Value of the output == 2^(E_t-127) * (1 + ((M >> r_t) + b_t)/128), computed from the
+    text fixture in float64."""
+    tab = _table1_from_text()
+    x = wl.all_bf16_patterns()
+    y = oracle.ktanh_bf16(x)
+    mag = x & 0x7FFF
+    region = (mag >= 0x3E80) & (mag < 0x4080)
+    assert region.sum() == 2 * 32 * 16
+    xs = x[region].astype(np.int64)
+    E, M = (xs >> 7) & 0xFF, xs & 0x7F
+    t = ((E & 3) << 3) | (M >> 4)
+    Et = np.array([tab[k][0] for k in t]); rt = np.array([tab[k][1] for k in t])
+    bt = np.array([tab[k][2] for k in t])
+    expect = np.ldexp(1.0 + ((M >> rt) + bt) / 128.0, Et - 127) * np.where(xs & 0x8000, -1.0, 1.0)
+    assert np.array_equal(_bf16_val(y[region]), expect)
+
+
+def test_bf16_odd_symmetry_exhaustive(oracle):
+    x = wl.all_bf16_patterns()
+    assert np.array_equal(oracle.ktanh_bf16(x ^ 0x8000), oracle.ktanh_bf16(x) ^ 0x8000)
+
+
+def test_bf16_regions_exhaustive(oracle):
+    x = wl.all_bf16_patterns()
+    y = oracle.ktanh_bf16(x)
+    mag, sign = x & 0x7FFF, x & 0x8000
+    small = mag < 0x3E80                       # |x| < 0.25, incl. zeros and subnormals
+    big = (mag >= 0x4080) & (mag <= 0x7F80)    # |x| >= 4, incl. +-Inf
+    nan = mag > 0x7F80
+    assert small.sum() == 32000 and big.sum() == 32258 and nan.sum() == 254
+    assert np.array_equal(y[small], x[small])
+    assert np.array_equal(y[big], sign[big] | 0x3F80)
+    assert np.array_equal(y[nan], x[nan] | 0x0040)
+    # range: everything that is not NaN stays within [-1, 1]; table outputs within (0.25, 1)
+    assert np.all((y[~nan] & 0x7FFF) <= 0x3F80)
+    mid = ~(small | big | nan)
+    assert np.all(((y[mid] & 0x7FFF) >= 0x3E81) & ((y[mid] & 0x7FFF) <= 0x3F7F))
+
+
+def test_bf16_monotone_except_six_table_boundaries(oracle):
+    """Shift-and-add is non-decreasing inside an interval.  Across interval boundaries Table 1
+    steps down in exactly six places (e.g. 0x3E9F -> (125,0,-4): 31-4=27 but 0x3EA0 ->
+    (125,0,-6): 32-6=26); everywhere else the positive axis is non-decreasing."""
+    x = np.arange(0, 0x7F81, dtype=np.uint16)           # +0 .. +Inf in value order
+    y = oracle.ktanh_bf16(x).astype(np.int64)
+    down = np.nonzero(np.diff(y) < 0)[0] + 1
+    assert [hex(v) for v in down] == ["0x3ea0", "0x3ec0", "0x3ed0", "0x3ee0", "0x3ef0", "0x3f80"]
+    assert np.all(down % 16 == 0)                       # only ever at an interval boundary
+    assert np.all(np.diff(y)[down - 1] >= -2)
+
+
+def test_bf16_error_within_table2(oracle):
+    """Max abs error 1.67e-2 and relative error 3.03 % are what Table 2 reports for K-TanH."""
+    x = wl.all_bf16_patterns()
+    finite = (x & 0x7FFF) < 0x7F80
+    xv, yv = _bf16_val(x[finite]), _bf16_val(oracle.ktanh_bf16(x)[finite])
+    ref = np.tanh(xv)
+    assert np.max(np.abs(yv - ref)) <= 1.67e-2
+    nz = ref != 0
+    # in the pass-through region tanh(x) ~ x - x^3/3: relative error < 0.25^2/3 ~ 2.1 %
+    assert np.max(np.abs(yv[nz] - ref[nz]) / np.abs(ref[nz])) <= 3.03e-2
+    # and the approximation is not trivially loose: it beats a 1 % error on most of the table region
+    mid = (np.abs(xv) >= 0.25) & (np.abs(xv) < 4)
+    assert np.mean(np.abs(yv[mid] - ref[mid]) < 5e-3) > 0.8
+
+
+def test_custom_lut_is_honoured(oracle):
+    """A table with one entry changed changes exactly that interval's outputs."""
+    rows = _table1_from_text()
+    rows[24] = (126, 0, 60)
+    lut = oracle.OracleLut.from_tuples(rows)
+    x = wl.all_bf16_patterns()
+    a, b = oracle.ktanh_bf16(x), oracle.ktanh_bf16(x, lut)
+    changed = np.nonzero(a != b)[0]
+    assert set(changed.tolist()) == set(range(0x3F80, 0x3F90)) | set(range(0xBF80, 0xBF90))
+    assert np.array_equal(b[0x3F80:0x3F90], 0x3F00 + 60 + np.arange(16))
+
+
+# ---------------------------------------------------------------- Algorithm 1, Float32
+def _f32_probe_patterns():
+    rng = np.random.Generator(np.random.PCG64(7729))
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    parts = [hi, hi | 0xFFFF, hi | 0x8000, hi | 0x0001,
+             hi | rng.integers(0, 1 << 16, size=1 << 16, dtype=np.uint32),
+             rng.integers(0, 1 << 32, size=1 << 21, dtype=np.uint64).astype(np.uint32),
+             wl.f32_mixture(1 << 20)]
+    return np.concatenate(parts)
+
+
+def test_f32_truncation_invariant(oracle):
+    """Keeping only the top 16 bits commutes with K-TanH: both formats index the same table
+    with the same leading bits, and the low mantissa bits never carry into the top 7."""
+    u = _f32_probe_patterns()
+    y = oracle.ktanh_f32(u)
+    notnan = (u & 0x7FFFFFFF) <= 0x7F800000
+    top = (u >> 16).astype(np.uint16)
+    assert np.array_equal((y >> 16).astype(np.uint16)[notnan], oracle.ktanh_bf16(top)[notnan])
+    nan = ~notnan
+    assert np.array_equal(y[nan], u[nan] | 0x00400000)
+
+
+def test_f32_closed_form_and_error(oracle):
+    tab = _table1_from_text()
+    u = _f32_probe_patterns()
+    y = oracle.ktanh_f32(u)
+    mag = u & 0x7FFFFFFF
+    region = (mag >= 0x3E800000) & (mag < 0x40800000)
+    us = u[region].astype(np.int64)
+    E, M = (us >> 23) & 0xFF, us & 0x7FFFFF
+    t = ((E & 3) << 3) | (M >> 20)
+    Et = np.array([tab[k][0] for k in range(32)])[t]
+    rt = np.array([tab[k][1] for k in range(32)])[t]
+    bt = np.array([tab[k][2] for k in range(32)])[t]
+    expect = np.ldexp(1.0 + ((M >> rt) + bt * 65536) / 2.0 ** 23, Et - 127)
+    expect *= np.where(us >> 31, -1.0, 1.0)
+    assert np.array_equal(_f32_val(y[region]), expect)
+    # pass-through, saturation, and error against double tanh
+    small = mag < 0x3E800000
+    big = (mag >= 0x40800000) & (mag <= 0x7F800000)
+    assert np.array_equal(y[small], u[small])
+    assert np.array_equal(y[big], (u[big] & 0x80000000) | 0x3F800000)
+    fin = mag < 0x7F800000
+    assert np.max(np.abs(_f32_val(y[fin]) - np.tanh(_f32_val(u[fin])))) <= 1.67e-2
+
+
+def test_f32_odd_symmetry(oracle):
+    u = _f32_probe_patterns()
+    assert np.array_equal(oracle.ktanh_f32(u ^ 0x80000000), oracle.ktanh_f32(u) ^ 0x80000000)
+
+
+# ---------------------------------------------------------------- derived activations
+def _ulp_distance_bf16(a, b):
+    """Distance in BFloat16 steps between two non-NaN patterns (sign-magnitude -> ordered ints)."""
+    def key(v):
+        v = v.astype(np.int64)
+        return np.where(v & 0x8000, -(v & 0x7FFF), v & 0x7FFF)
+    return np.abs(key(a) - key(b))
+
+
+def _round_f64_to_bf16(v):
+    """float64 -> nearest BFloat16 bits via a float32 stop (enough for a 1-ulp comparison)."""
+    return wl.f32_to_bf16_bits(v.astype(np.float32))
+
+
+def test_derived_spot_values(oracle):
+    for op, xin, xout, *_ in read_golden("derived_spot_values.txt"):
+        got = getattr(oracle, op)(np.array([int(xin, 16)], dtype=np.uint16))[0]
+        assert int(got) == int(xout, 16), f"{op} {xin}: got {int(got):04X}, expected {xout}"
+
+
+def _finite_bf16():
+    x = wl.all_bf16_patterns()
+    return x[(x & 0x7FFF) < 0x7F80]
+
+
+def test_ksigmoid_matches_double_recomputation(oracle):
+    """(1 + K(x/2)) / 2 re-evaluated in float64 around the oracle's own K-TanH, which the tests
+    above pin: the composition, not K, is what is being checked here."""
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    k = _bf16_val(oracle.ktanh_bf16(_round_f64_to_bf16(xv / 2)))
+    want = (1.0 + k) / 2.0
+    got = oracle.ksigmoid(x)
+    assert np.max(_ulp_distance_bf16(got, _round_f64_to_bf16(want))) <= 1
+    true = 1.0 / (1.0 + np.exp(-xv.clip(-80, 80)))
+    assert np.max(np.abs(_bf16_val(got) - true)) <= 1.67e-2 / 2 + 2.0 ** -9
+    # a sigmoid: within [0, 1], and s(x) + s(-x) = 1 up to rounding of each side
+    assert np.all((_bf16_val(got) >= 0) & (_bf16_val(got) <= 1))
+    assert np.max(np.abs(_bf16_val(got) + _bf16_val(oracle.ksigmoid(x ^ 0x8000)) - 1.0)) <= 2.0 ** -8
+
+
+def test_kswish_matches_double_recomputation(oracle):
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    k = _bf16_val(oracle.ktanh_bf16(_round_f64_to_bf16(xv / 2)))
+    want = xv * (1.0 + k) / 2.0
+    got = oracle.kswish(x)
+    ok = np.abs(want) < 3.0e38
+    assert np.max(_ulp_distance_bf16(got[ok], _round_f64_to_bf16(want[ok]))) <= 1
+    true = xv / (1.0 + np.exp(-xv.clip(-80, 80)))
+    rel = np.abs(_bf16_val(got[ok]) - true[ok]) <= 1.67e-2 / 2 * np.abs(xv[ok]) + 2.0 ** -8 * np.abs(true[ok]) + 1e-38
+    assert np.all(rel)
+
+
+def test_kgelu_matches_double_recomputation(oracle):
+    """The argument of K is rounded to BFloat16, and K jumps at interval boundaries, so the
+    float64 re-evaluation is only comparable where both roundings of the argument agree."""
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    arg64 = np.sqrt(2.0 / np.pi) * (xv + 0.044715 * xv ** 3)
+    arg_bits = _round_f64_to_bf16(np.clip(arg64, -3e38, 3e38))
+    # the oracle's own float32 argument, rebuilt op by op in numpy float32
+    xf = xv.astype(np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        arg32 = np.float32(0.7978845608028654) * (xf + np.float32(0.044715) * ((xf * xf) * xf))
+    # comparable where both roundings of the argument land on the same K value
+    same_arg = oracle.ktanh_bf16(wl.f32_to_bf16_bits(arg32)) == oracle.ktanh_bf16(arg_bits)
+    assert same_arg.mean() > 0.99
+    k = _bf16_val(oracle.ktanh_bf16(arg_bits))
+    want = xv / 2.0 * (1.0 + k)
+    got = oracle.kgelu(x)
+    ok = same_arg & (np.abs(want) < 3.0e38)
+    assert np.max(_ulp_distance_bf16(got[ok], _round_f64_to_bf16(want[ok]))) <= 1
+    # against the tanh-form GELU itself, on the range an activation sees
+    rng_ok = np.abs(xv) <= 16
+    true = xv / 2.0 * (1.0 + np.tanh(arg64))
+    err = np.abs(_bf16_val(got[rng_ok]) - true[rng_ok])
+    assert np.max(err - 2.0 ** -8 * np.abs(true[rng_ok])) <= 1.67e-2 / 2 * 16
+
+
+# ---------------------------------------------------------------- LSTM cell
+def test_klstm_single_cell_by_hand(oracle):
+    """All four gates 0 and c = 1: i = f = o = 0.5, g = 0, c' = 0.5, K(0.5) = 0x3EF0 = 0.46875,
+    h' = 0.5 * 0.46875 = 0.234375 = 0x3E70."""
+    gates = np.zeros((1, 1, 4 * 8), dtype=np.uint16)
+    c0 = np.ones((1, 8), dtype=np.float32)
+    c1, h = oracle.klstm_cell(gates, c0)
+    assert np.all(c1 == np.float32(0.5)) and np.all(h == 0x3E70)
+
+
+def test_klstm_gate_order_and_layout(oracle):
+    """Saturate one gate block at a time: i|f|g|o blocks of width H inside each row."""
+    H = 8
+    big, neg = 0x4100, 0xC100           # +8, -8: sigmoid -> 1, 0; tanh -> +1, -1
+    c0 = np.full((1, H), 2.0, dtype=np.float32)
+
+    def run(i, f, g, o):
+        row = np.concatenate([np.full(H, v, dtype=np.uint16) for v in (i, f, g, o)])
+        return oracle.klstm_cell(row.reshape(1, 1, 4 * H), c0)
+
+    c1, h = run(neg, big, big, big)      # i=0,f=1: c' = c = 2, h' = K(2) = 0x3F77
+    assert np.all(c1 == 2.0) and np.all(h == 0x3F77)
+    c1, h = run(big, neg, big, big)      # i=1,f=0,g=+1: c' = 1, h' = K(1) = 0x3F41
+    assert np.all(c1 == 1.0) and np.all(h == 0x3F41)
+    c1, h = run(big, neg, neg, big)      # g=-1: c' = -1, h' = -K(1)
+    assert np.all(c1 == -1.0) and np.all(h == 0xBF41)
+    c1, h = run(big, neg, big, neg)      # o=0: h' = +0
+    assert np.all(c1 == 1.0) and np.all(h == 0x0000)
+
+
+def test_klstm_matches_double_recomputation_and_chains(oracle):
+    T, B, H = 5, 3, 16
+    gates, c0 = wl.lstm_cell_inputs(T, B, H)
+    c_all, h_all = oracle.klstm_cell(gates, c0)
+    # T calls of one step each give the same as one call of T steps
+    c = c0
+    for t in range(T):
+        c, h = oracle.klstm_cell(gates[t:t + 1], c)
+        assert np.array_equal(h[0], h_all[t])
+        # one step re-evaluated in float64 from the previous float32 state
+        prev = c0 if t == 0 else c_prev
+        g4 = gates[t].reshape(B, 4, H)
+        sig = lambda bits: (1.0 + _bf16_val(oracle.ktanh_bf16(_round_f64_to_bf16(_bf16_val(bits) / 2)))) / 2
+        c64 = sig(g4[:, 1]) * prev.astype(np.float64) + sig(g4[:, 0]) * _bf16_val(oracle.ktanh_bf16(g4[:, 2]))
+        assert np.max(np.abs(c64 - c)) <= 2.0 ** -22 * (1 + np.max(np.abs(c64)))
+        h64 = sig(g4[:, 3]) * _bf16_val(oracle.ktanh_bf16(wl.f32_to_bf16_bits(c)))
+        assert np.max(_ulp_distance_bf16(h[0], _round_f64_to_bf16(h64))) <= 1
+        c_prev = c
+    assert np.array_equal(c, c_all)
+
+
+# ---------------------------------------------------------------- the pins do bite
+@pytest.mark.parametrize("t,field,delta", [(9, 2, 1), (24, 1, 1), (16, 0, 1), (3, 2, -1)])
+def test_a_wrong_table_entry_is_caught_by_the_error_or_fit_pins(oracle, t, field, delta):
+    """Plant a mistake in a copy of the table (on the CPU) and see that it no longer equals the
+    printed one: guards the comparison helpers against vacuous passes."""
+    rows = _table1_from_text()
+    row = list(rows[t]); row[field] += delta; rows[t] = tuple(row)
+    assert oracle.OracleLut.from_tuples(rows).as_tuples() != _table1_from_text()
+    x = wl.all_bf16_patterns()
+    assert not np.array_equal(oracle.ktanh_bf16(x, oracle.OracleLut.from_tuples(rows)), oracle.ktanh_bf16(x))
