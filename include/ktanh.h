@@ -1,0 +1,121 @@
+/*
+ * libktanh -- K-TanH (arXiv:1909.07729) and the activations derived from it, as HIP kernels for
+ * AMD MI355X (gfx950) behind a plain C ABI.
+ *
+ * Conventions shared by every entry point
+ *   - Tensor pointers (`in`, `out`, `gates`, `c_in`, `c_out`, `h_out`) are DEVICE pointers owned
+ *     by the caller.  The library allocates nothing, frees nothing and keeps no pointer after the
+ *     call returns.
+ *   - `lut` is a HOST pointer to the 96-byte parameter table; it is read during the call and
+ *     travels to the GPU inside the kernel arguments.  NULL selects the paper's Table 1.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls only enqueue
+ *     work: they return without synchronising, keep no global state and may be issued from
+ *     several host threads.
+ *   - BFloat16 tensors are arrays of uint16_t bit patterns (s:1, E:8, M:7); Float32 tensors of
+ *     K-TanH are arrays of uint32_t bit patterns (s:1, E:8, M:23).  Tensors are dense and 1-D as
+ *     far as the library is concerned (any contiguous shape works).
+ *   - `out == in` (and `c_out == c_in`) is allowed; any other overlap is undefined.
+ *   - Pointers must be aligned to their element size (else KT_ERR_ALIGN).  When `in` and `out`
+ *     are congruent modulo 16 bytes the body runs on 128-bit accesses and the ragged ends are
+ *     peeled; otherwise a slower element-wise kernel is used.  Results are identical.
+ *   - n == 0 (or T, B or H == 0) returns KT_OK without launching anything.
+ *   - Errors are returned, never thrown; nothing is launched when an argument is rejected.  A
+ *     failed launch is reported as KT_ERR_HIP.
+ */
+#ifndef KTANH_H
+#define KTANH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KTANH_INTERVALS 32
+
+/* The three parameter tables T_E, T_r, T_b of Algorithm 1, 32 entries each (Table 1).
+ * Entry t serves the interval whose index string is t = (2 LSBs of E_i) << 3 | (3 MSBs of M_i):
+ * t = 8..15 covers [0.25, 0.5), 16..23 [0.5, 1), 24..31 [1, 2), 0..7 [2, 4). */
+typedef struct ktanh_lut {
+    uint8_t E[KTANH_INTERVALS]; /* biased output exponent E_t, 1..254                   */
+    uint8_t r[KTANH_INTERVALS]; /* right shift r_t applied to the input mantissa, 0..7  */
+    int8_t  b[KTANH_INTERVALS]; /* signed offset b_t added to the shifted mantissa      */
+} ktanh_lut_t;
+
+typedef void *ktanh_stream_t; /* a hipStream_t */
+
+typedef enum ktanh_status {
+    KT_OK = 0,
+    KT_ERR_NULL = 1,  /* a required pointer is NULL                                       */
+    KT_ERR_ALIGN = 2, /* a tensor pointer is not aligned to its element size              */
+    KT_ERR_LUT = 3,   /* the table fails ktanh_lut_validate                               */
+    KT_ERR_SHAPE = 4, /* klstm_cell: H not a multiple of 8, or a size product overflows   */
+    KT_ERR_HIP = 5    /* the HIP runtime refused the launch                               */
+} ktanh_status_t;
+
+/* Human-readable name of a status code; static storage. */
+const char *ktanh_status_string(ktanh_status_t status);
+
+/* Table 1 of the paper (optimised parameters for BFloat16 inputs).  Static storage: never free
+ * it, never write through it. */
+const ktanh_lut_t *ktanh_default_lut(void);
+
+/* Checks that a table cannot overflow or underflow the 7-bit output mantissa, which is what the
+ * bounds b_min and b_max of Section 2.4 (eq. (2)) guarantee for a fitted table: for every entry,
+ * 1 <= E <= 254, 0 <= r <= 7, and 0 <= (M >> r) + b <= 127 for all 16 mantissas M of its interval.
+ * Host-only; `lut` is a host pointer.  Returns KT_OK, KT_ERR_NULL or KT_ERR_LUT. */
+ktanh_status_t ktanh_lut_validate(const ktanh_lut_t *lut);
+
+/* K-TanH on BFloat16 (Algorithm 1; thresholds and index of Section 2.3):
+ *   |x| <  0.25 (T1)                      -> x unchanged (zeros and subnormals included)
+ *   |x| >= 4    (beyond T2 = 3.75 on the 8 exponent + 3 mantissa bits the test inspects;
+ *                +-Inf included)          -> +-1
+ *   otherwise                             -> (s_i, E_t, (M_i >> r_t) + b_t)
+ *   NaN                                   -> the same NaN with its quiet bit set
+ * in, out: device, n elements each. */
+ktanh_status_t ktanh_bf16(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
+                          ktanh_stream_t stream);
+
+/* K-TanH on Float32 (Algorithm 1; the paper states the method carries over to Float32 and gives
+ * parameters for BFloat16 only): same thresholds and index on the leading bits, the 8-bit
+ * parameters act on the 23-bit mantissa as M_o = (M_i >> r_t) + b_t * 2^16.  Truncating input and
+ * output to their top 16 bits gives exactly ktanh_bf16.  in, out: device, n elements each. */
+ktanh_status_t ktanh_f32(const uint32_t *in, uint32_t *out, size_t n, const ktanh_lut_t *lut,
+                         ktanh_stream_t stream);
+
+/* Activations derived from TanH (Section 1), BFloat16 in and out, n elements each, device.
+ * K below is ktanh_bf16 applied to the BFloat16 rounding (nearest even) of its argument; all other
+ * arithmetic is IEEE Float32, one rounding per operation, the result rounded to BFloat16 (nearest
+ * even).  NaN in gives NaN out (which NaN is unspecified).
+ *   ksigmoid(x) = 0.5 * K(0.5 x) + 0.5
+ *   kswish(x)   = x * (0.5 * K(0.5 x) + 0.5)               (the Float32 Sigmoid, not re-rounded)
+ *   kgelu(x)    = (0.5 x) * (1 + K(c * (x + a * ((x*x)*x)))),  a = 0.044715f, c = sqrt(2/pi) as float
+ */
+ktanh_status_t ksigmoid(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
+                        ktanh_stream_t stream);
+ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
+                      ktanh_stream_t stream);
+ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
+                     ktanh_stream_t stream);
+
+/* Element-wise part of an LSTM cell with K-TanH non-linearities (the recurrent GNMT workload of
+ * Section 3 is what it serves; Sigmoid as in Section 1), over T consecutive time steps whose gate
+ * pre-activations are all given:
+ *   gates [T][B][4H] BFloat16, device: each row holds the blocks i | f | g | o, H values each
+ *   c_in  [B][H]     Float32,  device: cell state before the first step
+ *   c_out [B][H]     Float32,  device: cell state after the last step (may be c_in)
+ *   h_out [T][B][H]  BFloat16, device: hidden output of every step
+ * Per cell and step, in Float32:  i, f, o = 0.5*K(0.5 g_.)+0.5;  g = K(g_g);
+ *   c' = (f*c) + (i*g);  h' = bf16(o * K(bf16(c'))).   The state is carried in registers between
+ * the T steps.  T == 1 is the ordinary per-step call of a recurrent network.
+ * H must be a multiple of 8 (KT_ERR_SHAPE); all four tensors need 16-byte alignment
+ * (KT_ERR_ALIGN). */
+ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                          size_t T, size_t B, size_t H, const ktanh_lut_t *lut,
+                          ktanh_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KTANH_H */

@@ -1,0 +1,176 @@
+"""Python front-end of the C-ABI library ``libktanh.so``: argument marshalling only.
+
+Each function below has the name of the C entry point it calls (``include/ktanh.h``).  Tensors are
+``torch`` CUDA tensors used purely as device memory; every step of the computation runs inside the
+library's HIP kernels, on the current torch stream.  There is no fallback: if the library has not
+been built, or a call is rejected, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libktanh.so")
+INTERVALS = 32
+
+EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "ktanh_bf16",
+           "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell")
+
+
+class KtanhLut(ctypes.Structure):
+    """Mirror of ``ktanh_lut_t``: the tables T_E, T_r, T_b of Algorithm 1, indexed by t."""
+
+    _fields_ = [
+        ("E", ctypes.c_uint8 * INTERVALS),
+        ("r", ctypes.c_uint8 * INTERVALS),
+        ("b", ctypes.c_int8 * INTERVALS),
+    ]
+
+    @classmethod
+    def from_tuples(cls, rows):
+        lut = cls()
+        for t, (E, r, b) in enumerate(rows):
+            lut.E[t], lut.r[t], lut.b[t] = E, r, b
+        return lut
+
+    def as_tuples(self):
+        return [(int(self.E[t]), int(self.r[t]), int(self.b[t])) for t in range(INTERVALS)]
+
+
+class KtanhError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libktanh.so (once).  Raises if it is missing: build it with ``__graft_entry__.build()``."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        lp, vp, sz = ctypes.POINTER(KtanhLut), ctypes.c_void_p, ctypes.c_size_t
+        lib.ktanh_status_string.argtypes = [ctypes.c_int]
+        lib.ktanh_status_string.restype = ctypes.c_char_p
+        lib.ktanh_default_lut.argtypes = []
+        lib.ktanh_default_lut.restype = lp
+        lib.ktanh_lut_validate.argtypes = [lp]
+        lib.ktanh_lut_validate.restype = ctypes.c_int
+        for name in ("ktanh_bf16", "ktanh_f32", "ksigmoid", "kswish", "kgelu"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, sz, lp, vp]
+            fn.restype = ctypes.c_int
+        lib.klstm_cell.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp, vp]
+        lib.klstm_cell.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().ktanh_status_string(int(status)).decode()
+
+
+def ktanh_default_lut() -> KtanhLut:
+    """A copy of the library's built-in table (Table 1 of the paper)."""
+    src = load_library().ktanh_default_lut().contents
+    dst = KtanhLut()
+    ctypes.memmove(ctypes.byref(dst), ctypes.byref(src), ctypes.sizeof(KtanhLut))
+    return dst
+
+
+def ktanh_lut_validate(lut: KtanhLut | None) -> int:
+    return load_library().ktanh_lut_validate(ctypes.byref(lut) if lut is not None else None)
+
+
+def _stream_handle(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _lut_arg(lut):
+    return None if lut is None else ctypes.byref(lut)
+
+
+_BF16_VIEWS = (torch.bfloat16, torch.int16, torch.uint16)
+_F32_VIEWS = (torch.float32, torch.int32, torch.uint32)
+
+
+def _check(t: torch.Tensor, dtypes, what: str):
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a CUDA tensor (device memory)")
+    if t.dtype not in dtypes:
+        raise TypeError(f"{what} has dtype {t.dtype}, expected one of {dtypes}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+
+
+def _elementwise(name, x, out, lut, stream, dtypes):
+    _check(x, dtypes, "in")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(out, dtypes, "out")
+    if out.numel() != x.numel():
+        raise ValueError("in and out differ in size")
+    st = getattr(load_library(), name)(x.data_ptr(), out.data_ptr(), x.numel(), _lut_arg(lut),
+                                       _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, name)
+    return out
+
+
+def ktanh_bf16(x, out=None, lut=None, stream=None):
+    """K-TanH on a BFloat16 tensor (or its int16/uint16 bit view); ``out`` may be ``x``."""
+    return _elementwise("ktanh_bf16", x, out, lut, stream, _BF16_VIEWS)
+
+
+def ktanh_f32(x, out=None, lut=None, stream=None):
+    """K-TanH on a Float32 tensor (or its int32/uint32 bit view)."""
+    return _elementwise("ktanh_f32", x, out, lut, stream, _F32_VIEWS)
+
+
+def ksigmoid(x, out=None, lut=None, stream=None):
+    return _elementwise("ksigmoid", x, out, lut, stream, _BF16_VIEWS)
+
+
+def kswish(x, out=None, lut=None, stream=None):
+    return _elementwise("kswish", x, out, lut, stream, _BF16_VIEWS)
+
+
+def kgelu(x, out=None, lut=None, stream=None):
+    return _elementwise("kgelu", x, out, lut, stream, _BF16_VIEWS)
+
+
+def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None):
+    """LSTM-cell element-wise step(s).  gates [T, B, 4H] BFloat16 (i|f|g|o), c_in [B, H] Float32.
+
+    Returns (c_out [B, H] Float32, h_out [T, B, H] in the dtype of ``gates``).
+    """
+    _check(gates, _BF16_VIEWS, "gates")
+    _check(c_in, (torch.float32,), "c_in")
+    if gates.dim() != 3 or c_in.dim() != 2:
+        raise ValueError("gates must be [T, B, 4H] and c_in [B, H]")
+    T, B, H4 = gates.shape
+    H = H4 // 4
+    if H4 != 4 * H or tuple(c_in.shape) != (B, H):
+        raise ValueError("gates [T, B, 4H] and c_in [B, H] do not agree")
+    if c_out is None:
+        c_out = torch.empty_like(c_in)
+    if h_out is None:
+        h_out = torch.empty((T, B, H), dtype=gates.dtype, device=gates.device)
+    _check(c_out, (torch.float32,), "c_out")
+    _check(h_out, _BF16_VIEWS, "h_out")
+    if tuple(c_out.shape) != (B, H) or tuple(h_out.shape) != (T, B, H):
+        raise ValueError("c_out must be [B, H] and h_out [T, B, H]")
+    st = load_library().klstm_cell(gates.data_ptr(), c_in.data_ptr(), c_out.data_ptr(),
+                                   h_out.data_ptr(), T, B, H, _lut_arg(lut), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "klstm_cell")
+    return c_out, h_out

@@ -1,0 +1,34 @@
+"""Builds libktanh.so (the C-ABI library with the gfx950 kernels) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(_HERE)
+CSRC = os.path.join(_HERE, "csrc")
+LIB_PATH = os.path.join(_HERE, "libktanh.so")
+SOURCES = ["ktanh_kernels.hip", "ktanh_lut.cpp"]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-std=c++17", "-O3", "-fPIC", "-shared",
+    "-ffp-contract=off",                       # every fused multiply-add in the kernels is explicit
+    "-fno-gpu-flush-denormals-to-zero",        # Float32 subnormals are kept
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+]
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every source of the library for gfx950; returns the path of the .so."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return LIB_PATH
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

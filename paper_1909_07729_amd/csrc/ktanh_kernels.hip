@@ -1,0 +1,474 @@
+// libktanh device code and entry points: K-TanH (arXiv:1909.07729, Algorithm 1) and the
+// activations built on it, for gfx950.
+//
+// Shape of every kernel: a pure HBM stream.  Each lane moves 128 bits per access (8 BFloat16 or
+// 4 Float32), a wavefront covers 1 KiB per access, several accesses are in flight per lane, and the
+// integer work of Algorithm 1 is done on two BFloat16 values per 32-bit register with packed 16-bit
+// instructions.  The parameter table is spread over the 64 lanes of each wavefront (one slot per
+// lane) and read with ds_bpermute_b32, which needs neither LDS storage nor a barrier.
+//
+// Because a cross-lane read returns 0 from a disabled lane, every table read below executes with
+// the whole wavefront enabled: bounds only ever predicate the loads and stores around it.
+#include <hip/hip_runtime.h>
+
+#include "ktanh_pack.h"
+
+namespace {
+
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 256;   // 4 wavefronts
+constexpr int kUnroll = 4;    // 128-bit accesses in flight per lane
+constexpr uint32_t kMag2 = 0x7FFF7FFFu;
+
+__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
+__device__ __forceinline__ i16x2 as_i16x2(uint32_t w) { return __builtin_bit_cast(i16x2, w); }
+__device__ __forceinline__ uint32_t as_u32(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t as_u32(i16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ u16x2 splat(uint16_t v) { return u16x2{v, v}; }
+
+// 0xFFFF in each 16-bit half whose sign bit is set, 0 elsewhere: one packed arithmetic shift.
+// (Written as an instruction because the optimiser would otherwise turn "shift, then select on
+// the mask" into per-half compares and selects, which costs three times the issue slots.)
+__device__ __forceinline__ uint32_t sign_mask_pair(uint32_t d2)
+{
+    uint32_t m;
+    asm("v_pk_ashrrev_i16 %0, 15, %1 op_sel_hi:[0,1]" : "=v"(m) : "v"(d2));
+    return m;
+}
+
+// (a & mask) | (b & ~mask): one v_bfi_b32.
+__device__ __forceinline__ uint32_t bitsel(uint32_t mask, uint32_t a, uint32_t b)
+{
+    return (a & mask) | (b & ~mask);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The parameter table, one slot per lane (KtLutPack layout).  get() takes a byte address whose
+// bits [7:2] name the slot; higher bits are ignored by the instruction (lane = address / 4 mod 64).
+struct LaneTable {
+    uint32_t mine;
+    __device__ __forceinline__ explicit LaneTable(const KtLutPack &pack)
+        : mine(pack.slot[threadIdx.x & 63])
+    {
+    }
+    __device__ __forceinline__ uint32_t get(uint32_t slot_times_4) const
+    {
+        return (uint32_t)__builtin_amdgcn_ds_bpermute((int)slot_times_4, (int)mine);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 1 on two BFloat16 magnitudes held in one register (sign bits clear, NaN not handled).
+//   slot      = low six bits of (E_i, M_i[6:4]) after clamping |x| to 4.0, so that everything
+//               beyond T2 reads the saturation slot and needs no test of its own;
+//   table out = base_t + (M_i >> r_t), base_t = (E_t << 7) + b_t;
+//   |x| < T1  = input passed through.
+__device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTable &tab)
+{
+    const uint32_t mc2 = as_u32(__builtin_elementwise_min(as_u16x2(mag2), splat(0x4080)));
+    const uint32_t e_lo = tab.get(mc2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
+    const uint32_t e_hi = tab.get(mc2 >> 18);  // same bits of the high value
+    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
+    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
+    const u16x2 shifted = as_u16x2(mc2 & 0x007F007Fu) >> as_u16x2(r2);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + shifted);
+    // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
+    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    return bitsel(pass, mag2, lut2);
+}
+
+// 0xFFFF in each half that holds a NaN magnitude (> 0x7F80).
+__device__ __forceinline__ uint32_t nan_mask_pair(uint32_t mag2)
+{
+    return sign_mask_pair(as_u32(as_i16x2(0x7F807F80u) - as_i16x2(mag2)));
+}
+
+// K-TanH of two BFloat16 values, signs and NaNs included.
+__device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
+{
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t res = bitsel(kMag2, ktanh_mag_pair(mag2, tab), w);
+    return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
+}
+
+// Algorithm 1 on one Float32 pattern: same slot from the same leading bits; the 8-bit parameters
+// act on the 23-bit mantissa, b_t aligned to its top seven bits.
+__device__ __forceinline__ uint32_t ktanh_f32_one(uint32_t u, const LaneTable &tab)
+{
+    const uint32_t mag = u & 0x7FFFFFFFu;
+    const uint32_t mc = mag < 0x40800000u ? mag : 0x40800000u;
+    const uint32_t e = tab.get(mc >> 18);  // bits [7:2] <- bits [25:20]
+    const uint32_t lut = (e & 0xFFFF0000u) + ((mc & 0x007FFFFFu) >> (e & 31u));
+    uint32_t res = mag < 0x3E800000u ? mag : lut;
+    res = mag > 0x7F800000u ? (mag | 0x00400000u) : res;
+    return res | (u & 0x80000000u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// BFloat16 <-> Float32.
+__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Two Float32 -> two BFloat16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
+{
+    const bf16x2 h = __builtin_convertvector(f32x2{lo, hi}, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// 0.5 * K(0.5 x) + 0.5 in Float32 for both halves of w.
+//   Halving a BFloat16 is "exponent field minus one" whenever that field is at least 2; below that
+//   |x| < 2^-125, K passes its argument through and the result is 0.5 whatever the argument, so a
+//   saturating subtract of 0x80 from the magnitude stands for the multiply and the rounding.
+//   0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse.
+__device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &tab, float &s_lo,
+                                                  float &s_hi)
+{
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t half_mag2 = as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x0080)));
+    uint32_t t2 = bitsel(kMag2, ktanh_mag_pair(half_mag2, tab), w);
+    t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
+    s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
+    s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+}
+
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
+
+template <int OP>
+__device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
+{
+    if constexpr (OP == OP_TANH) {
+        return ktanh_pair(w, tab);
+    } else if constexpr (OP == OP_SIGMOID) {
+        float s_lo, s_hi;
+        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        return narrow_pair(s_lo, s_hi);
+    } else if constexpr (OP == OP_SWISH) {
+        float s_lo, s_hi;
+        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        return narrow_pair(widen_lo(w) * s_lo, widen_hi(w) * s_hi);
+    } else {
+        // GELU, tanh form: (x/2) * (1 + K(c * (x + a * x^3))).  (x/2) * (1 + t) and
+        // x * (0.5 + 0.5 t) are the same real product and round alike (halving is exact).
+        const float a = 0.044715f;
+        const float c = 0.7978845608028654f;
+        const float x_lo = widen_lo(w), x_hi = widen_hi(w);
+        const float u_lo = c * (x_lo + a * ((x_lo * x_lo) * x_lo));
+        const float u_hi = c * (x_hi + a * ((x_hi * x_hi) * x_hi));
+        const uint32_t t2 = ktanh_pair(narrow_pair(u_lo, u_hi), tab);
+        const float y_lo = x_lo * __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
+        const float y_hi = x_hi * __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+        return narrow_pair(y_lo, y_hi);
+    }
+}
+
+template <int OP>
+__device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
+{
+    return uint4{apply_pair<OP>(v.x, tab), apply_pair<OP>(v.y, tab), apply_pair<OP>(v.z, tab),
+                 apply_pair<OP>(v.w, tab)};
+}
+
+__device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
+{
+    return uint4{ktanh_f32_one(v.x, tab), ktanh_f32_one(v.y, tab), ktanh_f32_one(v.z, tab),
+                 ktanh_f32_one(v.w, tab)};
+}
+
+// ---------------------------------------------------------------------------------------------
+// Element-wise streaming kernel over `nvec` 128-bit vectors plus up to `n_edge` loose elements.
+//   vin, vout : 16-byte aligned body (nvec vectors)
+//   ein, eout : the whole tensor as elements; edge element k (k < n_head) is element k, edge
+//               element k >= n_head is element n_total - n_edge + k (the ragged tail)
+// F32 selects the Float32 K-TanH (OP ignored), else the BFloat16 operation OP.
+struct EdgeArgs {
+    const void *ein;
+    void *eout;
+    unsigned long long n_total;
+    unsigned n_head;
+    unsigned n_edge;  // head + tail elements, < 64
+};
+
+template <bool F32, int OP>
+__device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
+{
+    if constexpr (F32) return apply_vec_f32(v, tab);
+    else return apply_vec_bf16<OP>(v, tab);
+}
+
+template <bool F32, int OP>
+__global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict__ vin,
+                                                        uint4 *__restrict__ vout,
+                                                        unsigned long long nvec, EdgeArgs edge,
+                                                        KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    constexpr unsigned long long kTile = (unsigned long long)kBlock * kUnroll;
+    const unsigned long long full_tiles = nvec / kTile;
+
+    for (unsigned long long tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
+        const unsigned long long at = tile * kTile + threadIdx.x;
+        uint4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = vin[at + (unsigned long long)u * kBlock];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP>(v[u], tab);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) vout[at + (unsigned long long)u * kBlock] = v[u];
+    }
+
+    // Partial last tile: the last block takes it, bounds predicate only the memory accesses.
+    const unsigned long long rest_at = full_tiles * kTile;
+    if (rest_at < nvec && blockIdx.x == gridDim.x - 1) {
+        for (unsigned long long base = rest_at; base < nvec; base += kBlock) {
+            const unsigned long long i = base + threadIdx.x;
+            const bool live = i < nvec;
+            uint4 v = uint4{0u, 0u, 0u, 0u};
+            if (live) v = vin[i];
+            v = apply_vec<F32, OP>(v, tab);
+            if (live) vout[i] = v;
+        }
+    }
+
+    // Loose elements before and after the aligned body: first wavefront of block 0.
+    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+        const unsigned k = threadIdx.x;
+        const bool live = k < edge.n_edge;
+        const unsigned long long i =
+            k < edge.n_head ? k : edge.n_total - edge.n_edge + k;
+        uint32_t x = 0;
+        if constexpr (F32) {
+            if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
+            x = ktanh_f32_one(x, tab);
+            if (live) static_cast<uint32_t *>(edge.eout)[i] = x;
+        } else {
+            if (live) x = static_cast<const uint16_t *>(edge.ein)[i];
+            x = apply_pair<OP>(x, tab);
+            if (live) static_cast<uint16_t *>(edge.eout)[i] = (uint16_t)x;
+        }
+    }
+}
+
+// Fallback when `in` and `out` disagree modulo 16 bytes: one element per lane and pass.
+template <bool F32, int OP>
+__global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict__ in,
+                                                         void *__restrict__ out,
+                                                         unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n;
+         base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool live = i < n;
+        uint32_t x = 0;
+        if constexpr (F32) {
+            if (live) x = static_cast<const uint32_t *>(in)[i];
+            x = ktanh_f32_one(x, tab);
+            if (live) static_cast<uint32_t *>(out)[i] = x;
+        } else {
+            if (live) x = static_cast<const uint16_t *>(in)[i];
+            x = apply_pair<OP>(x, tab);
+            if (live) static_cast<uint16_t *>(out)[i] = (uint16_t)x;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// LSTM cell: each lane owns 8 neighbouring cells of one batch row and carries their state through
+// all T steps.  Per step it reads four 128-bit gate vectors (i, f, g, o) and writes one 128-bit h.
+struct CellPair {
+    float lo, hi;
+};
+
+__global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint4 *__restrict__ gates,
+                                                           const float4 *__restrict__ c_in,
+                                                           float4 *__restrict__ c_out,
+                                                           uint4 *__restrict__ h_out,
+                                                           unsigned T, unsigned long long n_cellvec,
+                                                           unsigned H8, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long v = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const bool live = v < n_cellvec;
+    const unsigned long long b = live ? v / H8 : 0;
+    const unsigned long long jv = live ? v % H8 : 0;
+
+    float c[8];
+    {
+        float4 c0 = float4{0.f, 0.f, 0.f, 0.f}, c1 = c0;
+        if (live) { c0 = c_in[2 * v]; c1 = c_in[2 * v + 1]; }
+        c[0] = c0.x; c[1] = c0.y; c[2] = c0.z; c[3] = c0.w;
+        c[4] = c1.x; c[5] = c1.y; c[6] = c1.z; c[7] = c1.w;
+    }
+
+    const unsigned long long row_step = n_cellvec * 4;  // gate vectors per time step
+    const uint4 *gp = gates + b * 4ull * H8 + jv;
+    uint4 *hp = h_out + v;
+    for (unsigned t = 0; t < T; ++t) {
+        uint4 gi = uint4{0u, 0u, 0u, 0u}, gf = gi, gg = gi, go = gi;
+        if (live) {
+            gi = gp[0];
+            gf = gp[H8];
+            gg = gp[2ull * H8];
+            go = gp[3ull * H8];
+        }
+        const uint32_t wi[4] = {gi.x, gi.y, gi.z, gi.w};
+        const uint32_t wf[4] = {gf.x, gf.y, gf.z, gf.w};
+        const uint32_t wg[4] = {gg.x, gg.y, gg.z, gg.w};
+        const uint32_t wo[4] = {go.x, go.y, go.z, go.w};
+        uint32_t hw[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
+            ksigmoid_f32_pair(wi[k], tab, i_lo, i_hi);
+            ksigmoid_f32_pair(wf[k], tab, f_lo, f_hi);
+            ksigmoid_f32_pair(wo[k], tab, o_lo, o_hi);
+            const uint32_t g2 = ktanh_pair(wg[k], tab);
+            // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
+            const float keep_lo = f_lo * c[2 * k], keep_hi = f_hi * c[2 * k + 1];
+            const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
+            const float c_lo = keep_lo + add_lo, c_hi = keep_hi + add_hi;
+            c[2 * k] = c_lo;
+            c[2 * k + 1] = c_hi;
+            const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
+            hw[k] = narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
+        }
+        if (live) *hp = uint4{hw[0], hw[1], hw[2], hw[3]};
+        gp += row_step;
+        hp += n_cellvec;
+    }
+    if (live) {
+        c_out[2 * v] = float4{c[0], c[1], c[2], c[3]};
+        c_out[2 * v + 1] = float4{c[4], c[5], c[6], c[7]};
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side.
+int compute_units()
+{
+    static int cached = 0;  // benign race: every thread computes the same value
+    if (cached == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached = cus;
+    }
+    return cached;
+}
+
+constexpr unsigned kBlocksPerCu = 8;  // resident blocks per compute unit the grid is sized for
+
+template <bool F32, int OP>
+ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const ktanh_lut_t *lut,
+                                  ktanh_stream_t stream)
+{
+    constexpr size_t kElem = F32 ? 4 : 2;
+    constexpr size_t kPerVec = 16 / kElem;
+    if (n == 0) return KT_OK;
+    if (in == nullptr || out == nullptr) return KT_ERR_NULL;
+    const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
+    if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 60) return KT_ERR_SHAPE;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut(lut, &pack);
+    if (st != KT_OK) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned max_blocks = (unsigned)compute_units() * kBlocksPerCu;
+
+    if ((ain & 15) == (aout & 15)) {
+        size_t head = ((16 - (ain & 15)) & 15) / kElem;
+        if (head > n) head = n;
+        const size_t nvec = (n - head) / kPerVec;
+        const size_t tail = n - head - nvec * kPerVec;
+        EdgeArgs edge;
+        edge.ein = in;
+        edge.eout = out;
+        edge.n_total = n;
+        edge.n_head = (unsigned)head;
+        edge.n_edge = (unsigned)(head + tail);
+        const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
+        uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
+        const size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
+        unsigned blocks = (unsigned)(tiles < max_blocks ? tiles : max_blocks);
+        if (blocks == 0) blocks = 1;
+        hipLaunchKernelGGL((stream_kernel<F32, OP>), dim3(blocks), dim3(kBlock), 0, s, vin, vout,
+                           (unsigned long long)nvec, edge, pack);
+    } else {
+        const size_t want = (n + kBlock - 1) / kBlock;
+        const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
+        hipLaunchKernelGGL((element_kernel<F32, OP>), dim3(blocks), dim3(kBlock), 0, s, in, out,
+                           (unsigned long long)n, pack);
+    }
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t ktanh_bf16(const uint16_t *in, uint16_t *out, size_t n,
+                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TANH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh_f32(const uint32_t *in, uint32_t *out, size_t n,
+                                    const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_TANH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid(const uint16_t *in, uint16_t *out, size_t n,
+                                   const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n,
+                                 const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n,
+                                const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out,
+                                     uint16_t *h_out, size_t T, size_t B, size_t H,
+                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (T == 0 || B == 0 || H == 0) return KT_OK;
+    if (gates == nullptr || c_in == nullptr || c_out == nullptr || h_out == nullptr)
+        return KT_ERR_NULL;
+    if (H % 8 != 0) return KT_ERR_SHAPE;
+    // sizes: T*B*4H elements must stay far below 2^63, T and H/8 must fit 32 bits
+    if (T > 0xFFFFFFFFull || H / 8 > 0xFFFFFFFFull || B > ((size_t)1 << 40) ||
+        (B * (H / 8)) > ((size_t)1 << 40) / T)
+        return KT_ERR_SHAPE;
+    const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_in) |
+                          reinterpret_cast<uintptr_t>(c_out) | reinterpret_cast<uintptr_t>(h_out);
+    if (mis & 15) return KT_ERR_ALIGN;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut(lut, &pack);
+    if (st != KT_OK) return st;
+
+    const unsigned long long n_cellvec = (unsigned long long)B * (H / 8);
+    const unsigned long long blocks = (n_cellvec + kBlock - 1) / kBlock;
+    if (blocks > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint4 *>(gates),
+                       reinterpret_cast<const float4 *>(c_in), reinterpret_cast<float4 *>(c_out),
+                       reinterpret_cast<uint4 *>(h_out), (unsigned)T, n_cellvec, (unsigned)(H / 8),
+                       pack);
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}

@@ -1,0 +1,74 @@
+// Host side of libktanh: the paper's parameter table, its validation and its kernel-argument form.
+#include "ktanh_pack.h"
+
+namespace {
+
+// Table 1 (optimised parameters for BFloat16 inputs), stored by integer index
+// t = (E_i & 3) << 3 | (M_i >> 4); the paper prints the rows by descending input magnitude.
+constexpr ktanh_lut_t kTable1 = {
+    /* E */ {// t = 0..7  : |x| in [2, 4)
+             126, 126, 126, 126, 126, 126, 126, 126,
+             // t = 8..15 : [0.25, 0.5)
+             125, 125, 125, 125, 125, 125, 125, 125,
+             // t = 16..23: [0.5, 1)
+             125, 126, 126, 126, 126, 126, 126, 126,
+             // t = 24..31: [1, 2)
+             126, 126, 126, 126, 126, 126, 126, 126},
+    /* r */ {2, 4, 4, 4, 6, 6, 6, 6,
+             1, 0, 0, 0, 0, 0, 0, 0,
+             0, 1, 1, 1, 1, 1, 1, 1,
+             0, 1, 1, 1, 2, 2, 2, 4},
+    /* b */ {119, 122, 123, 123, 126, 126, 126, 126,
+             1, -4, -6, -7, -10, -12, -15, -18,
+             112, -4, -1, 2, 3, 4, 4, 4,
+             65, 72, 73, 73, 88, 89, 89, 110},
+};
+
+}  // namespace
+
+extern "C" const char *ktanh_status_string(ktanh_status_t status)
+{
+    switch (status) {
+        case KT_OK: return "KT_OK";
+        case KT_ERR_NULL: return "KT_ERR_NULL: required pointer is NULL";
+        case KT_ERR_ALIGN: return "KT_ERR_ALIGN: pointer not aligned for its element type";
+        case KT_ERR_LUT: return "KT_ERR_LUT: parameter table would overflow the output mantissa";
+        case KT_ERR_SHAPE: return "KT_ERR_SHAPE: unsupported tensor shape";
+        case KT_ERR_HIP: return "KT_ERR_HIP: HIP runtime error at launch";
+    }
+    return "unknown ktanh status";
+}
+
+extern "C" const ktanh_lut_t *ktanh_default_lut(void) { return &kTable1; }
+
+// The output mantissa (M >> r) + b must stay a 7-bit unsigned number over the whole interval
+// (this is what b_min and b_max of Section 2.4 enforce when a table is fitted); shift-and-add is
+// monotone in M, so the interval's first and last mantissa decide.
+extern "C" ktanh_status_t ktanh_lut_validate(const ktanh_lut_t *lut)
+{
+    if (lut == nullptr) return KT_ERR_NULL;
+    for (int t = 0; t < KTANH_INTERVALS; ++t) {
+        const int E = lut->E[t], r = lut->r[t], b = lut->b[t];
+        if (E < 1 || E > 254 || r > 7) return KT_ERR_LUT;
+        const int m_first = (t & 7) << 4, m_last = m_first + 15;
+        if ((m_first >> r) + b < 0 || (m_last >> r) + b > 127) return KT_ERR_LUT;
+    }
+    return KT_OK;
+}
+
+ktanh_status_t kt_pack_lut(const ktanh_lut_t *lut, KtLutPack *pack)
+{
+    if (lut == nullptr) lut = &kTable1;
+    const ktanh_status_t st = ktanh_lut_validate(lut);
+    if (st != KT_OK) return st;
+    const uint32_t one = 0x3F80u << 16;  // +1.0, shift irrelevant (the clamped mantissa is zero)
+    for (int s = 0; s < 64; ++s) pack->slot[s] = one;
+    for (int t = 0; t < KTANH_INTERVALS; ++t) {
+        const uint32_t base = (uint32_t)((lut->E[t] << 7) + lut->b[t]);
+        const uint32_t word = (base << 16) | lut->r[t];
+        // strings 1000..1031: 1000 & 63 = 40, and string & 31 = t
+        const int string = 1000 + ((t - (1000 & 31)) & 31);
+        pack->slot[string & 63] = word;
+    }
+    return KT_OK;
+}

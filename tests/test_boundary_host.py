@@ -1,0 +1,90 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, carries the paper's table, validates tables, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from conftest import ROOT, read_golden
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_1909_07729_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_1909_07729_amd import build
+        build.build_library()
+    b.load_library()
+    return b
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ktanh.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(k\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(binding):
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    lib = binding.load_library()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layout_is_96_bytes(binding):
+    assert ctypes.sizeof(binding.KtanhLut) == 96
+
+
+def test_default_lut_is_table1(binding):
+    want = [None] * 32
+    for bits, E, r, b in read_golden("table1_bf16.txt"):
+        want[int(bits, 2)] = (int(E), int(r), int(b))
+    assert binding.ktanh_default_lut().as_tuples() == want
+    assert binding.ktanh_lut_validate(binding.ktanh_default_lut()) == 0
+
+
+def test_lut_validation(binding):
+    assert binding.ktanh_lut_validate(None) == 1
+    rows = binding.ktanh_default_lut().as_tuples()
+
+    def status(t, row):
+        bad = list(rows); bad[t] = row
+        return binding.ktanh_lut_validate(binding.KtanhLut.from_tuples(bad))
+
+    assert status(0, (126, 2, 120)) == 0          # still inside 0..127: (15 >> 2) + 120 = 123
+    assert status(7, (126, 6, 127)) == 3          # (127 >> 6) + 127 = 128 overflows the mantissa
+    assert status(9, (125, 0, -17)) == 3          # (16 >> 0) - 17 < 0 underflows
+    assert status(3, (126, 8, 0)) == 3            # shift beyond the mantissa width
+    assert status(3, (0, 1, 0)) == 3 and status(3, (255, 1, 0)) == 3   # exponent field out of range
+    assert status(15, (125, 0, -112)) == 0        # b_min of the interval with mantissa_idx_val 7
+    assert status(15, (125, 0, -113)) == 3
+
+
+def test_argument_errors_are_returned_before_any_launch(binding):
+    lib = binding.load_library()
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)                # never dereferenced: rejected on the host
+    for name in ("ktanh_bf16", "ktanh_f32", "ksigmoid", "kswish", "kgelu"):
+        fn = getattr(lib, name)
+        assert fn(null, null, 0, None, null) == 0             # n == 0: nothing to do
+        assert fn(null, fake, 8, None, null) == 1
+        assert fn(fake, null, 8, None, null) == 1
+        assert fn(ctypes.c_void_p(0x1001), fake, 8, None, null) == 2
+    assert lib.ktanh_f32(ctypes.c_void_p(0x1002), fake, 8, None, null) == 2
+    bad = binding.KtanhLut.from_tuples([(126, 9, 0)] * 32)
+    assert lib.ktanh_bf16(fake, fake, 8, ctypes.byref(bad), null) == 3
+    # LSTM cell
+    assert lib.klstm_cell(null, null, null, null, 0, 4, 8, None, null) == 0
+    assert lib.klstm_cell(null, fake, fake, fake, 1, 4, 8, None, null) == 1
+    assert lib.klstm_cell(fake, fake, fake, fake, 1, 4, 12, None, null) == 4
+    assert lib.klstm_cell(ctypes.c_void_p(0x1008), fake, fake, fake, 1, 4, 8, None, null) == 2
+    assert lib.klstm_cell(fake, fake, fake, fake, 1, 4, 8, ctypes.byref(bad), null) == 3
+    assert b"KT_ERR_LUT" in lib.ktanh_status_string(3)
+
+
+def test_binding_refuses_host_tensors(binding):
+    import torch
+    with pytest.raises(ValueError):
+        binding.ktanh_bf16(torch.zeros(8, dtype=torch.bfloat16))

@@ -1,0 +1,219 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+bytes.  Integer paths (ktanh_bf16, ktanh_f32) must match bit for bit.  The derived activations and
+the LSTM cell do their Float32 steps in the oracle's order, so they are held to the same bar --
+identical bits -- which is tighter than the 1 BFloat16 ulp they are allowed; only a NaN may differ
+in sign or payload (compared as a class).
+"""
+import numpy as np
+import pytest
+
+from paper_1909_07729_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BF16_OPS = ("ktanh_bf16", "ksigmoid", "kswish", "kgelu")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1909_07729_amd import binding
+    binding.load_library()          # no fallback: a missing library fails the whole module
+    torch.cuda.set_device(0)
+    return binding, torch
+
+
+def _to_dev(torch, a):
+    view = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32}.get(a.dtype, a.dtype)
+    return torch.from_numpy(np.ascontiguousarray(a).view(view)).to("cuda:0")
+
+
+def _to_host(t, dtype):
+    return t.cpu().numpy().view(dtype)
+
+
+def _assert_bf16_equal(got, want, exact_nan, what):
+    if exact_nan:
+        bad = np.nonzero(got != want)[0]
+    else:
+        gn, wn = (got & 0x7FFF) > 0x7F80, (want & 0x7FFF) > 0x7F80
+        assert np.array_equal(gn, wn), f"{what}: NaN positions differ"
+        bad = np.nonzero((got != want) & ~wn)[0]
+    assert bad.size == 0, (f"{what}: {bad.size} mismatches, first at {bad[0]}: "
+                           f"got {int(got[bad[0]]):04X} want {int(want[bad[0]]):04X}")
+
+
+def _run_bf16(gpu, oracle, name, x, lut_rows=None):
+    binding, torch = gpu
+    klut = binding.KtanhLut.from_tuples(lut_rows) if lut_rows else None
+    olut = oracle.OracleLut.from_tuples(lut_rows) if lut_rows else None
+    got = _to_host(getattr(binding, name)(_to_dev(torch, x), lut=klut), np.uint16)
+    want = getattr(oracle, name)(x, olut)
+    _assert_bf16_equal(got, want, name == "ktanh_bf16", f"{name} n={x.size}")
+
+
+# ------------------------------------------------------------------ all 65,536 patterns
+@pytest.mark.parametrize("name", BF16_OPS)
+def test_exhaustive_bf16_patterns(gpu, oracle, name):
+    _run_bf16(gpu, oracle, name, wl.all_bf16_patterns())
+
+
+def test_exhaustive_bf16_patterns_shuffled_and_custom_lut(gpu, oracle):
+    rng = np.random.Generator(np.random.PCG64(11))
+    x = rng.permutation(wl.all_bf16_patterns())
+    rows = oracle.table1().as_tuples()
+    rows[24] = (126, 0, 60); rows[9] = (125, 1, 3); rows[7] = (127, 7, 0); rows[16] = (124, 3, 100)
+    for name in BF16_OPS:
+        _run_bf16(gpu, oracle, name, x, rows)
+
+
+def test_f32_structured_patterns(gpu, oracle):
+    binding, torch = gpu
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    rng = np.random.Generator(np.random.PCG64(12))
+    u = np.concatenate([hi, hi | 0xFFFF, hi | 0x8000, hi | 1,
+                        rng.integers(0, 1 << 32, size=(1 << 22) + 3, dtype=np.uint64).astype(np.uint32)])
+    got = _to_host(binding.ktanh_f32(_to_dev(torch, u)), np.uint32)
+    assert np.array_equal(got, oracle.ktanh_f32(u))
+
+
+# ------------------------------------------------------------------ ragged sizes, alignment, aliasing
+@pytest.mark.parametrize("n", [1, 2, 7, 8, 9, 63, 64, 65, 1023, 8191, 8192, 8193, 8192 * 3 + 5,
+                               256 * 4 * 8 * 7 + 8 * 300 + 3])
+def test_ragged_sizes(gpu, oracle, n):
+    x = wl.lstm_gate_preactivations(n, seed=1000 + n)
+    x[:: max(1, n // 7)] = wl.edge_bf16_patterns()[: len(x[:: max(1, n // 7)])]
+    for name in BF16_OPS:
+        _run_bf16(gpu, oracle, name, x)
+    binding, torch = gpu
+    u = wl.f32_mixture(n, seed=2000 + n)
+    got = _to_host(binding.ktanh_f32(_to_dev(torch, u)), np.uint32)
+    assert np.array_equal(got, oracle.ktanh_f32(u))
+
+
+@pytest.mark.parametrize("in_off,out_off", [(0, 0), (1, 1), (3, 3), (7, 7), (0, 1), (5, 2), (1, 0)])
+def test_unaligned_views(gpu, oracle, in_off, out_off):
+    """Element offsets into 16-byte aligned buffers: congruent offsets take the vector body with
+    peeled ends, different ones the element-wise kernel.  Guard bytes around `out` stay intact."""
+    binding, torch = gpu
+    n = 8192 * 2 + 11
+    x = wl.mlp_preactivations(n + 16, seed=31)
+    xd = _to_dev(torch, x)
+    for name in BF16_OPS:
+        outd = torch.full((n + 32,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        getattr(binding, name)(xd[in_off:in_off + n], out=outd[8 + out_off:8 + out_off + n])
+        res = _to_host(outd, np.uint16)
+        want = getattr(oracle, name)(x[in_off:in_off + n])
+        _assert_bf16_equal(res[8 + out_off:8 + out_off + n], want, name == "ktanh_bf16", name)
+        assert np.all(res[:8 + out_off] == 0x5A5A) and np.all(res[8 + out_off + n:] == 0x5A5A)
+    u = wl.f32_mixture(n + 8, seed=32)
+    ud = _to_dev(torch, u)
+    i4, o4 = in_off % 4, out_off % 4
+    outd = torch.full((n + 16,), 0x5A5A5A5A, dtype=torch.int32, device="cuda:0")
+    binding.ktanh_f32(ud[i4:i4 + n], out=outd[4 + o4:4 + o4 + n])
+    res = _to_host(outd, np.uint32)
+    assert np.array_equal(res[4 + o4:4 + o4 + n], oracle.ktanh_f32(u[i4:i4 + n]))
+    assert np.all(res[:4 + o4] == 0x5A5A5A5A) and np.all(res[4 + o4 + n:] == 0x5A5A5A5A)
+
+
+def test_in_place_and_empty_and_stream(gpu, oracle):
+    binding, torch = gpu
+    x = wl.lstm_gate_preactivations(300007, seed=41)
+    for name in BF16_OPS:
+        xd = _to_dev(torch, x)
+        getattr(binding, name)(xd, out=xd)
+        _assert_bf16_equal(_to_host(xd, np.uint16), getattr(oracle, name)(x), name == "ktanh_bf16", name)
+    empty = torch.empty(0, dtype=torch.bfloat16, device="cuda:0")
+    assert binding.ktanh_bf16(empty).numel() == 0
+    side = torch.cuda.Stream()
+    xd = _to_dev(torch, x)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        yd = binding.ktanh_bf16(xd)
+    side.synchronize()
+    assert np.array_equal(_to_host(yd, np.uint16), oracle.ktanh_bf16(x))
+    # bfloat16-typed tensors go through unchanged
+    xb = _to_dev(torch, x).view(torch.bfloat16)
+    assert np.array_equal(_to_host(binding.ktanh_bf16(xb).view(torch.int16), np.uint16), oracle.ktanh_bf16(x))
+
+
+def test_rejected_calls_raise(gpu):
+    binding, torch = gpu
+    x = torch.zeros(64, dtype=torch.bfloat16, device="cuda:0")
+    bad = binding.KtanhLut.from_tuples([(126, 9, 0)] * 32)
+    with pytest.raises(binding.KtanhError) as e:
+        binding.ktanh_bf16(x, lut=bad)
+    assert e.value.status == 3
+    g = torch.zeros((1, 2, 4 * 12), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(binding.KtanhError) as e:
+        binding.klstm_cell(g, torch.zeros((2, 12), device="cuda:0"))
+    assert e.value.status == 4
+
+
+# ------------------------------------------------------------------ the named workloads, full size
+def test_lstm_gate_preactivations_full(gpu, oracle):
+    """[50, 128, 4096] BFloat16 ~ N(0, 1.5^2): the tensor the throughput figure is quoted on."""
+    _run_bf16(gpu, oracle, "ktanh_bf16", wl.lstm_gate_preactivations())
+
+
+def test_f32_mixture_full(gpu, oracle):
+    """2^28 Float32: uniform [-8, 8) with 5 % N(0, 0.01^2)."""
+    binding, torch = gpu
+    u = wl.f32_mixture()
+    got = _to_host(binding.ktanh_f32(_to_dev(torch, u)), np.uint32)
+    want = oracle.ktanh_f32(u)
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, f"{bad.size} mismatches, first {bad[:1]}"
+
+
+def test_mlp_preactivations_full(gpu, oracle):
+    """[8192, 16384] BFloat16 ~ N(0, 1) through Sigmoid, Swish and GELU."""
+    x = wl.mlp_preactivations()
+    for name in ("ksigmoid", "kswish", "kgelu"):
+        _run_bf16(gpu, oracle, name, x)
+
+
+# ------------------------------------------------------------------ LSTM cell
+def _lstm_check(gpu, oracle, gates, c0, per_step):
+    binding, torch = gpu
+    T = gates.shape[0]
+    gd, cd = _to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0")
+    if per_step:
+        hs = []
+        for t in range(T):
+            cd, h = binding.klstm_cell(gd[t:t + 1], cd, c_out=cd)      # state updated in place
+            hs.append(h)
+        hd = torch.cat(hs, dim=0)
+    else:
+        cd, hd = binding.klstm_cell(gd, cd)
+    c_ref, h_ref = oracle.klstm_cell(gates, c0)
+    c_got, h_got = cd.cpu().numpy(), _to_host(hd, np.uint16)
+    cn = np.isnan(c_ref)
+    assert np.array_equal(np.isnan(c_got), cn)
+    assert np.array_equal(c_got.view(np.uint32)[~cn], c_ref.view(np.uint32)[~cn])
+    _assert_bf16_equal(h_got.ravel(), h_ref.ravel(), False, "h_out")
+
+
+@pytest.mark.parametrize("T,B,H", [(1, 1, 8), (3, 5, 24), (4, 7, 2048 + 8), (2, 300, 64)])
+def test_lstm_cell_small(gpu, oracle, T, B, H):
+    gates, c0 = wl.lstm_cell_inputs(T, B, H)
+    _lstm_check(gpu, oracle, gates, c0, per_step=False)
+    _lstm_check(gpu, oracle, gates, c0, per_step=True)
+
+
+def test_lstm_cell_special_values(gpu, oracle):
+    T, B, H = 2, 2, 16
+    gates, c0 = wl.lstm_cell_inputs(T, B, H)
+    edge = wl.edge_bf16_patterns()
+    gates.reshape(-1)[: edge.size] = edge
+    c0.reshape(-1)[:6] = [np.inf, -np.inf, np.nan, 0.0, -0.0, 1e-40]
+    _lstm_check(gpu, oracle, gates, c0, per_step=False)
+
+
+def test_lstm_cell_full(gpu, oracle):
+    """gates [64, 256, 4 x 2048] ~ N(0, 2^2), c0 [256, 2048] ~ N(0, 1): one call over all 64 steps
+    and 64 calls of one step, both against the oracle."""
+    gates, c0 = wl.lstm_cell_inputs()
+    _lstm_check(gpu, oracle, gates, c0, per_step=False)
+    _lstm_check(gpu, oracle, gates, c0, per_step=True)
