@@ -50,7 +50,7 @@ typedef enum ktanh_status {
     KT_ERR_NULL = 1,  /* a required pointer is NULL                                       */
     KT_ERR_ALIGN = 2, /* a tensor pointer is not aligned to its element size              */
     KT_ERR_LUT = 3,   /* the table fails ktanh_lut_validate                               */
-    KT_ERR_SHAPE = 4, /* klstm_cell: H not a multiple of 8, or a size product overflows   */
+    KT_ERR_SHAPE = 4, /* klstm_cell: H not a multiple of 8; any entry point: tensor too large */
     KT_ERR_HIP = 5    /* the HIP runtime refused the launch                               */
 } ktanh_status_t;
 

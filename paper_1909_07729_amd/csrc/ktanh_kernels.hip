@@ -21,7 +21,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;   // 4 wavefronts
-constexpr int kUnroll = 4;    // 128-bit accesses in flight per lane
+constexpr int kUnroll = 2;    // 128-bit accesses per lane (8 KiB tile per block)
 constexpr uint32_t kMag2 = 0x7FFF7FFFu;
 
 __device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
@@ -136,6 +136,23 @@ __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &t
     s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
 }
 
+// 128-bit streaming accesses.  Stores carry the non-temporal hint: the output is not read again by
+// this kernel and plain stores cost about 5 % of the throughput on out-of-cache tensors.  Loads stay
+// plain: the hint gains 1 % on a tensor that comes from HBM and loses 6 % on one that the producer
+// left in the last-level cache, which is the common case for an activation.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 load_stream(const uint4 *p) { return *p; }
+__device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
+{
+    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+}
+[[maybe_unused]] __device__ __forceinline__ void store_stream(float4 *p, float4 v)
+{
+    __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(p));
+}
+
 enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
 
 template <int OP>
@@ -207,32 +224,21 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
                                                         KtLutPack pack)
 {
     const LaneTable tab(pack);
-    constexpr unsigned long long kTile = (unsigned long long)kBlock * kUnroll;
-    const unsigned long long full_tiles = nvec / kTile;
 
-    for (unsigned long long tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
-        const unsigned long long at = tile * kTile + threadIdx.x;
-        uint4 v[kUnroll];
+    // One tile of kBlock * kUnroll vectors per block, no loop: fresh blocks keep loads and stores
+    // of different tiles overlapped, which a grid-stride loop over the same tiles does not.
+    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
+    uint4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = vin[at + (unsigned long long)u * kBlock];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP>(v[u], tab);
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) vout[at + (unsigned long long)u * kBlock] = v[u];
+    for (int u = 0; u < kUnroll; ++u) {
+        v[u] = uint4{0u, 0u, 0u, 0u};
+        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
     }
-
-    // Partial last tile: the last block takes it, bounds predicate only the memory accesses.
-    const unsigned long long rest_at = full_tiles * kTile;
-    if (rest_at < nvec && blockIdx.x == gridDim.x - 1) {
-        for (unsigned long long base = rest_at; base < nvec; base += kBlock) {
-            const unsigned long long i = base + threadIdx.x;
-            const bool live = i < nvec;
-            uint4 v = uint4{0u, 0u, 0u, 0u};
-            if (live) v = vin[i];
-            v = apply_vec<F32, OP>(v, tab);
-            if (live) vout[i] = v;
-        }
-    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP>(v[u], tab);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, v[u]);
 
     // Loose elements before and after the aligned body: first wavefront of block 0.
     if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
@@ -281,9 +287,54 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
 // ---------------------------------------------------------------------------------------------
 // LSTM cell: each lane owns 8 neighbouring cells of one batch row and carries their state through
 // all T steps.  Per step it reads four 128-bit gate vectors (i, f, g, o) and writes one 128-bit h.
-struct CellPair {
-    float lo, hi;
+// The steps of one lane are sequential, so the gate vectors of the next kStages steps are already
+// on their way while a step is computed (a ring of register stages): without that the loop would
+// pay one full memory latency per step.
+constexpr int kStages = 4;
+
+struct GateVecs {
+    uint4 i, f, g, o;
 };
+
+__device__ __forceinline__ GateVecs load_gates(const uint4 *row, unsigned H8, bool live)
+{
+    GateVecs q;
+    q.i = q.f = q.g = q.o = uint4{0u, 0u, 0u, 0u};
+    if (live) {
+        q.i = load_stream(row);
+        q.f = load_stream(row + H8);
+        q.g = load_stream(row + 2ull * H8);
+        q.o = load_stream(row + 3ull * H8);
+    }
+    return q;
+}
+
+// One time step for the 8 cells of a lane: updates c, returns the 8 hidden outputs.
+__device__ __forceinline__ uint4 lstm_step(const GateVecs &q, float (&c)[8], const LaneTable &tab)
+{
+    const uint32_t wi[4] = {q.i.x, q.i.y, q.i.z, q.i.w};
+    const uint32_t wf[4] = {q.f.x, q.f.y, q.f.z, q.f.w};
+    const uint32_t wg[4] = {q.g.x, q.g.y, q.g.z, q.g.w};
+    const uint32_t wo[4] = {q.o.x, q.o.y, q.o.z, q.o.w};
+    uint32_t hw[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
+        ksigmoid_f32_pair(wi[k], tab, i_lo, i_hi);
+        ksigmoid_f32_pair(wf[k], tab, f_lo, f_hi);
+        ksigmoid_f32_pair(wo[k], tab, o_lo, o_hi);
+        const uint32_t g2 = ktanh_pair(wg[k], tab);
+        // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
+        const float keep_lo = f_lo * c[2 * k], keep_hi = f_hi * c[2 * k + 1];
+        const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
+        const float c_lo = keep_lo + add_lo, c_hi = keep_hi + add_hi;
+        c[2 * k] = c_lo;
+        c[2 * k + 1] = c_hi;
+        const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
+        hw[k] = narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
+    }
+    return uint4{hw[0], hw[1], hw[2], hw[3]};
+}
 
 __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint4 *__restrict__ gates,
                                                            const float4 *__restrict__ c_in,
@@ -297,6 +348,13 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint4 *__restri
     const bool live = v < n_cellvec;
     const unsigned long long b = live ? v / H8 : 0;
     const unsigned long long jv = live ? v % H8 : 0;
+    const unsigned long long row_step = n_cellvec * 4;  // gate vectors per time step
+    const uint4 *gp = gates + b * 4ull * H8 + jv;       // this lane's i-vector at step 0
+    uint4 *hp = h_out + v;
+
+    GateVecs stage[kStages];
+#pragma unroll
+    for (int s = 0; s < kStages; ++s) stage[s] = load_gates(gp + s * row_step, H8, live && s < (int)T);
 
     float c[8];
     {
@@ -306,41 +364,18 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint4 *__restri
         c[4] = c1.x; c[5] = c1.y; c[6] = c1.z; c[7] = c1.w;
     }
 
-    const unsigned long long row_step = n_cellvec * 4;  // gate vectors per time step
-    const uint4 *gp = gates + b * 4ull * H8 + jv;
-    uint4 *hp = h_out + v;
-    for (unsigned t = 0; t < T; ++t) {
-        uint4 gi = uint4{0u, 0u, 0u, 0u}, gf = gi, gg = gi, go = gi;
-        if (live) {
-            gi = gp[0];
-            gf = gp[H8];
-            gg = gp[2ull * H8];
-            go = gp[3ull * H8];
-        }
-        const uint32_t wi[4] = {gi.x, gi.y, gi.z, gi.w};
-        const uint32_t wf[4] = {gf.x, gf.y, gf.z, gf.w};
-        const uint32_t wg[4] = {gg.x, gg.y, gg.z, gg.w};
-        const uint32_t wo[4] = {go.x, go.y, go.z, go.w};
-        uint32_t hw[4];
+    for (unsigned t0 = 0; t0 < T; t0 += kStages) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
-            ksigmoid_f32_pair(wi[k], tab, i_lo, i_hi);
-            ksigmoid_f32_pair(wf[k], tab, f_lo, f_hi);
-            ksigmoid_f32_pair(wo[k], tab, o_lo, o_hi);
-            const uint32_t g2 = ktanh_pair(wg[k], tab);
-            // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
-            const float keep_lo = f_lo * c[2 * k], keep_hi = f_hi * c[2 * k + 1];
-            const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
-            const float c_lo = keep_lo + add_lo, c_hi = keep_hi + add_hi;
-            c[2 * k] = c_lo;
-            c[2 * k + 1] = c_hi;
-            const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
-            hw[k] = narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
+        for (int s = 0; s < kStages; ++s) {
+            const unsigned t = t0 + s;
+            if (t < T) {  // uniform over the grid: the table reads below keep every lane enabled
+                const GateVecs q = stage[s];
+                stage[s] = load_gates(gp + (unsigned long long)(t + kStages) * row_step, H8,
+                                      live && t + kStages < T);
+                const uint4 h = lstm_step(q, c, tab);
+                if (live) store_stream(hp + (unsigned long long)t * n_cellvec, h);
+            }
         }
-        if (live) *hp = uint4{hw[0], hw[1], hw[2], hw[3]};
-        gp += row_step;
-        hp += n_cellvec;
     }
     if (live) {
         c_out[2 * v] = float4{c[0], c[1], c[2], c[3]};
@@ -376,7 +411,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
     if (in == nullptr || out == nullptr) return KT_ERR_NULL;
     const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
     if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
-    if (n > (size_t)1 << 60) return KT_ERR_SHAPE;
+    if (n > (size_t)1 << 42) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
     KtLutPack pack;
     const ktanh_status_t st = kt_pack_lut(lut, &pack);
     if (st != KT_OK) return st;
@@ -397,11 +432,11 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
         edge.n_edge = (unsigned)(head + tail);
         const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
         uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
-        const size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
-        unsigned blocks = (unsigned)(tiles < max_blocks ? tiles : max_blocks);
-        if (blocks == 0) blocks = 1;
-        hipLaunchKernelGGL((stream_kernel<F32, OP>), dim3(blocks), dim3(kBlock), 0, s, vin, vout,
-                           (unsigned long long)nvec, edge, pack);
+        size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
+        if (tiles == 0) tiles = 1;  // edges only
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+        hipLaunchKernelGGL((stream_kernel<F32, OP>), dim3((unsigned)tiles), dim3(kBlock), 0, s, vin,
+                           vout, (unsigned long long)nvec, edge, pack);
     } else {
         const size_t want = (n + kBlock - 1) / kBlock;
         const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
