@@ -21,7 +21,6 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 256;   // 4 wavefronts
-constexpr int kUnroll = 2;    // 128-bit accesses per lane (8 KiB tile per block)
 constexpr uint32_t kMag2 = 0x7FFF7FFFu;
 
 __device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
@@ -136,21 +135,19 @@ __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &t
     s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
 }
 
-// 128-bit streaming accesses.  Stores carry the non-temporal hint: the output is not read again by
-// this kernel and plain stores cost about 5 % of the throughput on out-of-cache tensors.  Loads stay
-// plain: the hint gains 1 % on a tensor that comes from HBM and loses 6 % on one that the producer
-// left in the last-level cache, which is the common case for an activation.
+// 128-bit streaming accesses, all with the non-temporal hint: every byte is touched once.  Measured
+// on tensors that come from HBM: hinted stores are worth about 5 %, hinted loads another 1-3 %.
+// (On a tensor its producer left in the 256 MB last-level cache the load hint costs about 4 %.)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint4 load_stream(const uint4 *p) { return *p; }
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return uint4{t.x, t.y, t.z, t.w};
+}
 __device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
 {
     __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
-}
-[[maybe_unused]] __device__ __forceinline__ void store_stream(float4 *p, float4 v)
-{
-    __builtin_nontemporal_store(f32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4 *>(p));
 }
 
 enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
@@ -217,7 +214,7 @@ __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
     else return apply_vec_bf16<OP>(v, tab);
 }
 
-template <bool F32, int OP>
+template <bool F32, int OP, int kUnroll>
 __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict__ vin,
                                                         uint4 *__restrict__ vout,
                                                         unsigned long long nvec, EdgeArgs edge,
@@ -226,7 +223,9 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
     const LaneTable tab(pack);
 
     // One tile of kBlock * kUnroll vectors per block, no loop: fresh blocks keep loads and stores
-    // of different tiles overlapped, which a grid-stride loop over the same tiles does not.
+    // of different tiles overlapped, which a grid-stride loop over the same tiles does not (measured:
+    // 6.5 against 6.0 TB/s on a 537 MB stream).  kUnroll = 1 moves the most bytes for the light
+    // operations; the Float32-heavy ones need two vectors per lane to hide their arithmetic.
     const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
     uint4 v[kUnroll];
 #pragma unroll
@@ -285,102 +284,86 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// LSTM cell: each lane owns 8 neighbouring cells of one batch row and carries their state through
-// all T steps.  Per step it reads four 128-bit gate vectors (i, f, g, o) and writes one 128-bit h.
-// The steps of one lane are sequential, so the gate vectors of the next kStages steps are already
-// on their way while a step is computed (a ring of register stages): without that the loop would
-// pay one full memory latency per step.
+// LSTM cell: each lane owns two neighbouring cells of one batch row (one packed BFloat16 pair per
+// gate) and carries their state through all T steps.  The work per cell is about sixty vector
+// instructions against ten bytes of traffic, so the kernel wants many wavefronts per SIMD to overlap
+// arithmetic with memory rather than wide accesses; a wavefront's loads still cover 256 contiguous
+// bytes each.  The steps of one lane are sequential, so the gate words of the next kStages steps are
+// already on their way while a step is computed (a ring of register stages): without that the loop
+// would pay one full memory latency per step.
 constexpr int kStages = 4;
 
-struct GateVecs {
-    uint4 i, f, g, o;
+struct GateWords {
+    uint32_t i, f, g, o;
 };
 
-__device__ __forceinline__ GateVecs load_gates(const uint4 *row, unsigned H8, bool live)
+__device__ __forceinline__ GateWords load_gates(const uint32_t *row, unsigned H2, bool live)
 {
-    GateVecs q;
-    q.i = q.f = q.g = q.o = uint4{0u, 0u, 0u, 0u};
+    GateWords q{0u, 0u, 0u, 0u};
     if (live) {
-        q.i = load_stream(row);
-        q.f = load_stream(row + H8);
-        q.g = load_stream(row + 2ull * H8);
-        q.o = load_stream(row + 3ull * H8);
+        q.i = row[0];
+        q.f = row[H2];
+        q.g = row[2ull * H2];
+        q.o = row[3ull * H2];
     }
     return q;
 }
 
-// One time step for the 8 cells of a lane: updates c, returns the 8 hidden outputs.
-__device__ __forceinline__ uint4 lstm_step(const GateVecs &q, float (&c)[8], const LaneTable &tab)
+// One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
+__device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
+                                              const LaneTable &tab)
 {
-    const uint32_t wi[4] = {q.i.x, q.i.y, q.i.z, q.i.w};
-    const uint32_t wf[4] = {q.f.x, q.f.y, q.f.z, q.f.w};
-    const uint32_t wg[4] = {q.g.x, q.g.y, q.g.z, q.g.w};
-    const uint32_t wo[4] = {q.o.x, q.o.y, q.o.z, q.o.w};
-    uint32_t hw[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
-        ksigmoid_f32_pair(wi[k], tab, i_lo, i_hi);
-        ksigmoid_f32_pair(wf[k], tab, f_lo, f_hi);
-        ksigmoid_f32_pair(wo[k], tab, o_lo, o_hi);
-        const uint32_t g2 = ktanh_pair(wg[k], tab);
-        // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
-        const float keep_lo = f_lo * c[2 * k], keep_hi = f_hi * c[2 * k + 1];
-        const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
-        const float c_lo = keep_lo + add_lo, c_hi = keep_hi + add_hi;
-        c[2 * k] = c_lo;
-        c[2 * k + 1] = c_hi;
-        const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
-        hw[k] = narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
-    }
-    return uint4{hw[0], hw[1], hw[2], hw[3]};
+    float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
+    ksigmoid_f32_pair(q.i, tab, i_lo, i_hi);
+    ksigmoid_f32_pair(q.f, tab, f_lo, f_hi);
+    ksigmoid_f32_pair(q.o, tab, o_lo, o_hi);
+    const uint32_t g2 = ktanh_pair(q.g, tab);
+    // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
+    const float keep_lo = f_lo * c_lo, keep_hi = f_hi * c_hi;
+    const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
+    c_lo = keep_lo + add_lo;
+    c_hi = keep_hi + add_hi;
+    const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
+    return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
 }
 
-__global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint4 *__restrict__ gates,
-                                                           const float4 *__restrict__ c_in,
-                                                           float4 *__restrict__ c_out,
-                                                           uint4 *__restrict__ h_out,
-                                                           unsigned T, unsigned long long n_cellvec,
-                                                           unsigned H8, KtLutPack pack)
+__global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
+                                                           const float2 *__restrict__ c_in,
+                                                           float2 *__restrict__ c_out,
+                                                           uint32_t *__restrict__ h_out, unsigned T,
+                                                           unsigned long long n_pairs, unsigned H2,
+                                                           KtLutPack pack)
 {
     const LaneTable tab(pack);
-    const unsigned long long v = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
-    const bool live = v < n_cellvec;
-    const unsigned long long b = live ? v / H8 : 0;
-    const unsigned long long jv = live ? v % H8 : 0;
-    const unsigned long long row_step = n_cellvec * 4;  // gate vectors per time step
-    const uint4 *gp = gates + b * 4ull * H8 + jv;       // this lane's i-vector at step 0
-    uint4 *hp = h_out + v;
+    const unsigned long long p = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const bool live = p < n_pairs;
+    const unsigned long long b = live ? p / H2 : 0;
+    const unsigned long long j = live ? p % H2 : 0;
+    const unsigned long long row_step = n_pairs * 4;   // gate words per time step
+    const uint32_t *gp = gates + b * 4ull * H2 + j;     // this lane's i-word at step 0
+    uint32_t *hp = h_out + p;
 
-    GateVecs stage[kStages];
+    GateWords stage[kStages];
 #pragma unroll
-    for (int s = 0; s < kStages; ++s) stage[s] = load_gates(gp + s * row_step, H8, live && s < (int)T);
+    for (int s = 0; s < kStages; ++s) stage[s] = load_gates(gp + s * row_step, H2, live && s < (int)T);
 
-    float c[8];
-    {
-        float4 c0 = float4{0.f, 0.f, 0.f, 0.f}, c1 = c0;
-        if (live) { c0 = c_in[2 * v]; c1 = c_in[2 * v + 1]; }
-        c[0] = c0.x; c[1] = c0.y; c[2] = c0.z; c[3] = c0.w;
-        c[4] = c1.x; c[5] = c1.y; c[6] = c1.z; c[7] = c1.w;
-    }
+    float2 c = float2{0.f, 0.f};
+    if (live) c = c_in[p];
 
     for (unsigned t0 = 0; t0 < T; t0 += kStages) {
 #pragma unroll
         for (int s = 0; s < kStages; ++s) {
             const unsigned t = t0 + s;
             if (t < T) {  // uniform over the grid: the table reads below keep every lane enabled
-                const GateVecs q = stage[s];
-                stage[s] = load_gates(gp + (unsigned long long)(t + kStages) * row_step, H8,
+                const GateWords q = stage[s];
+                stage[s] = load_gates(gp + (unsigned long long)(t + kStages) * row_step, H2,
                                       live && t + kStages < T);
-                const uint4 h = lstm_step(q, c, tab);
-                if (live) store_stream(hp + (unsigned long long)t * n_cellvec, h);
+                const uint32_t h = lstm_step(q, c.x, c.y, tab);
+                if (live) __builtin_nontemporal_store(h, hp + (unsigned long long)t * n_pairs);
             }
         }
     }
-    if (live) {
-        c_out[2 * v] = float4{c[0], c[1], c[2], c[3]};
-        c_out[2 * v + 1] = float4{c[4], c[5], c[6], c[7]};
-    }
+    if (live) c_out[p] = c;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -411,7 +394,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
     if (in == nullptr || out == nullptr) return KT_ERR_NULL;
     const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
     if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
-    if (n > (size_t)1 << 42) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
     KtLutPack pack;
     const ktanh_status_t st = kt_pack_lut(lut, &pack);
     if (st != KT_OK) return st;
@@ -432,11 +415,12 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
         edge.n_edge = (unsigned)(head + tail);
         const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
         uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
+        constexpr int kUnroll = (F32 || OP == OP_TANH) ? 1 : 2;
         size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        hipLaunchKernelGGL((stream_kernel<F32, OP>), dim3((unsigned)tiles), dim3(kBlock), 0, s, vin,
-                           vout, (unsigned long long)nvec, edge, pack);
+        hipLaunchKernelGGL((stream_kernel<F32, OP, kUnroll>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                           s, vin, vout, (unsigned long long)nvec, edge, pack);
     } else {
         const size_t want = (n + kBlock - 1) / kBlock;
         const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
@@ -487,7 +471,7 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
         return KT_ERR_NULL;
     if (H % 8 != 0) return KT_ERR_SHAPE;
     // sizes: T*B*4H elements must stay far below 2^63, T and H/8 must fit 32 bits
-    if (T > 0xFFFFFFFFull || H / 8 > 0xFFFFFFFFull || B > ((size_t)1 << 40) ||
+    if (T > 0x7FFFFFFFull || H / 2 > 0xFFFFFFFFull || B > ((size_t)1 << 40) ||
         (B * (H / 8)) > ((size_t)1 << 40) / T)
         return KT_ERR_SHAPE;
     const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_in) |
@@ -497,13 +481,13 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
     const ktanh_status_t st = kt_pack_lut(lut, &pack);
     if (st != KT_OK) return st;
 
-    const unsigned long long n_cellvec = (unsigned long long)B * (H / 8);
-    const unsigned long long blocks = (n_cellvec + kBlock - 1) / kBlock;
+    const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
+    const unsigned long long blocks = (n_pairs + kBlock - 1) / kBlock;
     if (blocks > 0x7FFFFFFFull) return KT_ERR_SHAPE;
     hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint4 *>(gates),
-                       reinterpret_cast<const float4 *>(c_in), reinterpret_cast<float4 *>(c_out),
-                       reinterpret_cast<uint4 *>(h_out), (unsigned)T, n_cellvec, (unsigned)(H / 8),
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
+                       reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
+                       reinterpret_cast<uint32_t *>(h_out), (unsigned)T, n_pairs, (unsigned)(H / 2),
                        pack);
     return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
 }

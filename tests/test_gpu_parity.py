@@ -217,3 +217,36 @@ def test_lstm_cell_full(gpu, oracle):
     gates, c0 = wl.lstm_cell_inputs()
     _lstm_check(gpu, oracle, gates, c0, per_step=False)
     _lstm_check(gpu, oracle, gates, c0, per_step=True)
+
+
+def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
+    """Every entry point only enqueues kernels, so a stream capture records them; each replay is
+    checked against the oracle, with eager work and synchronisation between the replays."""
+    binding, torch = gpu
+    x = wl.lstm_gate_preactivations(200000, seed=77)
+    gates, c0 = wl.lstm_cell_inputs(6, 8, 64)
+    xd, gd = _to_dev(torch, x), _to_dev(torch, gates)
+    cd = torch.from_numpy(c0).to("cuda:0")
+    yd, sd = torch.empty_like(xd), torch.empty_like(xd)
+    hd = torch.empty((6, 8, 64), dtype=torch.int16, device="cuda:0")
+    cw = torch.empty_like(cd)
+    binding.ktanh_bf16(xd, out=yd)                       # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.ktanh_bf16(xd, out=yd)
+        binding.kgelu(xd, out=sd)
+        cw.copy_(cd)
+        for t in range(6):
+            binding.klstm_cell(gd[t:t + 1], cw, c_out=cw, h_out=hd[t:t + 1])
+    want_y, want_s = oracle.ktanh_bf16(x), oracle.kgelu(x)
+    want_c, want_h = oracle.klstm_cell(gates, c0)
+    for replay in range(3):
+        yd.fill_(0); sd.fill_(0); hd.fill_(0); cw.fill_(0)          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(_to_host(yd, np.uint16), want_y), f"replay {replay}"
+        _assert_bf16_equal(_to_host(sd, np.uint16), want_s, False, f"kgelu replay {replay}")
+        assert np.array_equal(cw.cpu().numpy(), want_c), f"replay {replay}"
+        assert np.array_equal(_to_host(hd, np.uint16), want_h), f"replay {replay}"
