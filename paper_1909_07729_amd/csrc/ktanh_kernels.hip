@@ -64,7 +64,10 @@ struct LaneTable {
 // Algorithm 1 on two BFloat16 magnitudes held in one register (sign bits clear, NaN not handled).
 //   slot      = low six bits of (E_i, M_i[6:4]) after clamping |x| to 4.0, so that everything
 //               beyond T2 reads the saturation slot and needs no test of its own;
-//   table out = base_t + (M_i >> r_t), base_t = (E_t << 7) + b_t;
+//   table out = (E_t << 7) + b_t + (M_i >> r_t).  Every slot belongs to one input exponent E_i, and
+//               (|x| >> r) = (E_i << (7 - r)) + (M_i >> r) exactly for r <= 7, so the slot stores
+//               base_t = (E_t << 7) + b_t - (E_i << (7 - r_t)) and the magnitude is shifted whole:
+//               no mantissa mask.  (The saturation slot shifts by 15, which leaves 0.)
 //   |x| < T1  = input passed through.
 __device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTable &tab)
 {
@@ -73,8 +76,7 @@ __device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTabl
     const uint32_t e_hi = tab.get(mc2 >> 18);  // same bits of the high value
     const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
     const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
-    const u16x2 shifted = as_u16x2(mc2 & 0x007F007Fu) >> as_u16x2(r2);
-    const uint32_t lut2 = as_u32(as_u16x2(base2) + shifted);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mc2) >> as_u16x2(r2)));
     // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
     const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
     return bitsel(pass, mag2, lut2);
@@ -86,12 +88,25 @@ __device__ __forceinline__ uint32_t nan_mask_pair(uint32_t mag2)
     return sign_mask_pair(as_u32(as_i16x2(0x7F807F80u) - as_i16x2(mag2)));
 }
 
-// K-TanH of two BFloat16 values, signs and NaNs included.
+// K-TanH of two BFloat16 values, signs included.  NANS = false leaves out the NaN rule (a NaN then
+// comes out as +-1): for callers that have already established that no NaN can reach this point.
+template <bool NANS = true>
 __device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
 {
     const uint32_t mag2 = w & kMag2;
     const uint32_t res = bitsel(kMag2, ktanh_mag_pair(mag2, tab), w);
+    if constexpr (!NANS) return res;
     return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
+}
+
+// True in a lane where any of the given BFloat16 magnitude pairs holds a NaN.
+__device__ __forceinline__ bool any_nan_pair(uint32_t mag2)
+{
+    return as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x7F80))) != 0u;
+}
+__device__ __forceinline__ uint32_t max_pair(uint32_t a2, uint32_t b2)
+{
+    return as_u32(__builtin_elementwise_max(as_u16x2(a2), as_u16x2(b2)));
 }
 
 // Algorithm 1 on one Float32 pattern: same slot from the same leading bits; the 8-bit parameters
@@ -101,6 +116,7 @@ __device__ __forceinline__ uint32_t ktanh_f32_one(uint32_t u, const LaneTable &t
     const uint32_t mag = u & 0x7FFFFFFFu;
     const uint32_t mc = mag < 0x40800000u ? mag : 0x40800000u;
     const uint32_t e = tab.get(mc >> 18);  // bits [7:2] <- bits [25:20]
+    // Float32 slots (kt_pack_lut_f32) keep the plain base (E_t << 7) + b_t in the high half.
     const uint32_t lut = (e & 0xFFFF0000u) + ((mc & 0x007FFFFFu) >> (e & 31u));
     uint32_t res = mag < 0x3E800000u ? mag : lut;
     res = mag > 0x7F800000u ? (mag | 0x00400000u) : res;
@@ -124,13 +140,15 @@ __device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
 //   |x| < 2^-125, K passes its argument through and the result is 0.5 whatever the argument, so a
 //   saturating subtract of 0x80 from the magnitude stands for the multiply and the rounding.
 //   0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse.
+template <bool NANS = true>
 __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &tab, float &s_lo,
                                                   float &s_hi)
 {
     const uint32_t mag2 = w & kMag2;
     const uint32_t half_mag2 = as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x0080)));
     uint32_t t2 = bitsel(kMag2, ktanh_mag_pair(half_mag2, tab), w);
-    t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
+    if constexpr (NANS)
+        t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
     s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
     s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
 }
@@ -297,33 +315,57 @@ struct GateWords {
     uint32_t i, f, g, o;
 };
 
-__device__ __forceinline__ GateWords load_gates(const uint32_t *row, unsigned H2, bool live)
+// Byte offsets of a lane's four gate words inside one time step's [B][4H] gate matrix: 32-bit, so
+// that each load is "uniform 64-bit base + 32-bit lane offset" and needs no address arithmetic.
+struct GateOffsets {
+    unsigned i, f, g, o;
+};
+
+__device__ __forceinline__ uint32_t load_word(const uint32_t *base, unsigned byte_offset)
 {
+    return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_offset);
+}
+
+__device__ __forceinline__ GateWords load_gates(const uint32_t *step_base, GateOffsets &at,
+                                                bool live)
+{
+    // The empty statement re-defines the four 32-bit offsets right where they are used, so that
+    // each access is selected as "scalar base + 32-bit vector offset"; otherwise their 64-bit
+    // extensions are hoisted out of the loop and every access pays a 64-bit vector add.
+    asm volatile("" : "+v"(at.i), "+v"(at.f), "+v"(at.g), "+v"(at.o));
     GateWords q{0u, 0u, 0u, 0u};
     if (live) {
-        q.i = row[0];
-        q.f = row[H2];
-        q.g = row[2ull * H2];
-        q.o = row[3ull * H2];
+        q.i = load_word(step_base, at.i);
+        q.f = load_word(step_base, at.f);
+        q.g = load_word(step_base, at.g);
+        q.o = load_word(step_base, at.o);
     }
     return q;
 }
 
+__device__ __forceinline__ bool not_finite(float x)
+{
+    return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u;
+}
+
 // One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
+// NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
+// is NaN and the incoming state is finite (the state then stays finite: |c'| <= |c| + 1).
+template <bool NANS>
 __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
                                               const LaneTable &tab)
 {
     float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
-    ksigmoid_f32_pair(q.i, tab, i_lo, i_hi);
-    ksigmoid_f32_pair(q.f, tab, f_lo, f_hi);
-    ksigmoid_f32_pair(q.o, tab, o_lo, o_hi);
-    const uint32_t g2 = ktanh_pair(q.g, tab);
+    ksigmoid_f32_pair<NANS>(q.i, tab, i_lo, i_hi);
+    ksigmoid_f32_pair<NANS>(q.f, tab, f_lo, f_hi);
+    ksigmoid_f32_pair<NANS>(q.o, tab, o_lo, o_hi);
+    const uint32_t g2 = ktanh_pair<NANS>(q.g, tab);
     // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
     const float keep_lo = f_lo * c_lo, keep_hi = f_hi * c_hi;
     const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
     c_lo = keep_lo + add_lo;
     c_hi = keep_hi + add_hi;
-    const uint32_t tc2 = ktanh_pair(narrow_pair(c_lo, c_hi), tab);
+    const uint32_t tc2 = ktanh_pair<NANS>(narrow_pair(c_lo, c_hi), tab);
     return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
 }
 
@@ -331,24 +373,31 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__res
                                                            const float2 *__restrict__ c_in,
                                                            float2 *__restrict__ c_out,
                                                            uint32_t *__restrict__ h_out, unsigned T,
-                                                           unsigned long long n_pairs, unsigned H2,
+                                                           unsigned n_pairs, unsigned H2,
                                                            KtLutPack pack)
 {
     const LaneTable tab(pack);
-    const unsigned long long p = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned p = blockIdx.x * kBlock + threadIdx.x;
     const bool live = p < n_pairs;
-    const unsigned long long b = live ? p / H2 : 0;
-    const unsigned long long j = live ? p % H2 : 0;
-    const unsigned long long row_step = n_pairs * 4;   // gate words per time step
-    const uint32_t *gp = gates + b * 4ull * H2 + j;     // this lane's i-word at step 0
-    uint32_t *hp = h_out + p;
+    const unsigned b = live ? p / H2 : 0;
+    const unsigned j = live ? p % H2 : 0;
+    const unsigned long long row_step = 4ull * n_pairs;  // gate words per time step
+    GateOffsets at;
+    at.i = (b * 4u * H2 + j) * 4u;  // < 16 * n_pairs <= 2^32 (checked by the caller)
+    at.f = at.i + 4u * H2;
+    at.g = at.f + 4u * H2;
+    at.o = at.g + 4u * H2;
+
+    unsigned h_at = 4u * p;  // byte offset of this lane's output word inside one step of h
 
     GateWords stage[kStages];
 #pragma unroll
-    for (int s = 0; s < kStages; ++s) stage[s] = load_gates(gp + s * row_step, H2, live && s < (int)T);
+    for (int s = 0; s < kStages; ++s)
+        stage[s] = load_gates(gates + s * row_step, at, live && s < (int)T);
 
     float2 c = float2{0.f, 0.f};
     if (live) c = c_in[p];
+    bool suspect = not_finite(c.x) || not_finite(c.y);
 
     for (unsigned t0 = 0; t0 < T; t0 += kStages) {
 #pragma unroll
@@ -356,10 +405,26 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__res
             const unsigned t = t0 + s;
             if (t < T) {  // uniform over the grid: the table reads below keep every lane enabled
                 const GateWords q = stage[s];
-                stage[s] = load_gates(gp + (unsigned long long)(t + kStages) * row_step, H2,
+                stage[s] = load_gates(gates + (unsigned long long)(t + kStages) * row_step, at,
                                       live && t + kStages < T);
-                const uint32_t h = lstm_step(q, c.x, c.y, tab);
-                if (live) __builtin_nontemporal_store(h, hp + (unsigned long long)t * n_pairs);
+                // NaNs are rare: one test per step for the whole wavefront picks the full rules
+                // only when some lane needs them (a wavefront-uniform branch, so that the
+                // cross-lane table reads still run with every lane enabled).
+                const uint32_t worst = max_pair(max_pair(q.i & kMag2, q.f & kMag2),
+                                                max_pair(q.g & kMag2, q.o & kMag2));
+                uint32_t h;
+                if (__builtin_amdgcn_ballot_w64(suspect || any_nan_pair(worst)) != 0) {
+                    h = lstm_step<true>(q, c.x, c.y, tab);
+                    suspect = not_finite(c.x) || not_finite(c.y);
+                } else {
+                    h = lstm_step<false>(q, c.x, c.y, tab);
+                }
+                asm volatile("" : "+v"(h_at));  // same reason as in load_gates
+                if (live) {
+                    uint32_t *h_step = h_out + (unsigned long long)t * n_pairs;
+                    __builtin_nontemporal_store(
+                        h, reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(h_step) + h_at));
+                }
             }
         }
     }
@@ -396,7 +461,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
     if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
     if (n > (size_t)1 << 40) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
     KtLutPack pack;
-    const ktanh_status_t st = kt_pack_lut(lut, &pack);
+    const ktanh_status_t st = F32 ? kt_pack_lut_f32(lut, &pack) : kt_pack_lut_bf16(lut, &pack);
     if (st != KT_OK) return st;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -478,16 +543,16 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
                           reinterpret_cast<uintptr_t>(c_out) | reinterpret_cast<uintptr_t>(h_out);
     if (mis & 15) return KT_ERR_ALIGN;
     KtLutPack pack;
-    const ktanh_status_t st = kt_pack_lut(lut, &pack);
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
     if (st != KT_OK) return st;
 
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
+    if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
     const unsigned long long blocks = (n_pairs + kBlock - 1) / kBlock;
-    if (blocks > 0x7FFFFFFFull) return KT_ERR_SHAPE;
     hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
                        reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
-                       reinterpret_cast<uint32_t *>(h_out), (unsigned)T, n_pairs, (unsigned)(H / 2),
-                       pack);
+                       reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
+                       (unsigned)(H / 2), pack);
     return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
 }

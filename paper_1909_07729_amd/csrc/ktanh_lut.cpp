@@ -56,19 +56,36 @@ extern "C" ktanh_status_t ktanh_lut_validate(const ktanh_lut_t *lut)
     return KT_OK;
 }
 
-ktanh_status_t kt_pack_lut(const ktanh_lut_t *lut, KtLutPack *pack)
+namespace {
+
+ktanh_status_t pack_slots(const ktanh_lut_t *lut, KtLutPack *pack, bool fold_input_exponent)
 {
     if (lut == nullptr) lut = &kTable1;
     const ktanh_status_t st = ktanh_lut_validate(lut);
     if (st != KT_OK) return st;
-    const uint32_t one = 0x3F80u << 16;  // +1.0, shift irrelevant (the clamped mantissa is zero)
+    // +1.0; the BFloat16 kernels shift the clamped magnitude 0x4080 out entirely, the Float32
+    // kernel shifts a zero mantissa
+    const uint32_t one = (0x3F80u << 16) | (fold_input_exponent ? 15u : 0u);
     for (int s = 0; s < 64; ++s) pack->slot[s] = one;
     for (int t = 0; t < KTANH_INTERVALS; ++t) {
-        const uint32_t base = (uint32_t)((lut->E[t] << 7) + lut->b[t]);
-        const uint32_t word = (base << 16) | lut->r[t];
-        // strings 1000..1031: 1000 & 63 = 40, and string & 31 = t
+        // strings 1000..1031 in order of t: 1000 & 31 = 8, and string & 31 = t
         const int string = 1000 + ((t - (1000 & 31)) & 31);
-        pack->slot[string & 63] = word;
+        const int r = lut->r[t];
+        int base = (lut->E[t] << 7) + lut->b[t];
+        if (fold_input_exponent) base -= (string >> 3) << (7 - r);  // string >> 3 = input exponent
+        pack->slot[string & 63] = ((uint32_t)(base & 0xFFFF) << 16) | (uint32_t)r;
     }
     return KT_OK;
+}
+
+}  // namespace
+
+ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack)
+{
+    return pack_slots(lut, pack, true);
+}
+
+ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack)
+{
+    return pack_slots(lut, pack, false);
 }

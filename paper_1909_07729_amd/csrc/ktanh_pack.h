@@ -8,11 +8,16 @@
 // (8 exponent bits, 3 leading mantissa bits) that Algorithm 1's threshold tests inspect.
 // Strings 1000..1031 (|x| in [0.25, 4)) land on slots 40..63, 0..7 and carry Table 1's entry for
 // t = string & 31; string 1032 (|x| clamped to 4) lands on slot 8 and carries the saturation
-// value 1.0.  A slot holds  ((E_t << 7) + b_t) << 16  |  r_t : the output magnitude for a zero
-// shifted mantissa in the high half, the shift in the low half.
+// value 1.0.  A slot holds  base << 16 | shift :
+//   BFloat16 kernels: base = (E_t << 7) + b_t - (E_i << (7 - r_t)), E_i the input exponent the slot
+//                     belongs to, so that base + (|x| >> r_t) is the output magnitude with no
+//                     mantissa mask; shift = r_t (15 in the saturation slot: |x| >> 15 = 0);
+//   Float32 kernel:   base = (E_t << 7) + b_t, to be aligned to the top of the word and added to
+//                     the shifted 23-bit mantissa; shift = r_t.
 struct KtLutPack {
     uint32_t slot[64];
 };
 
-// Validates `lut` (NULL = Table 1) and fills `pack`.
-ktanh_status_t kt_pack_lut(const ktanh_lut_t *lut, KtLutPack *pack);
+// Validate `lut` (NULL = Table 1) and fill `pack` for the BFloat16 kernels / the Float32 kernel.
+ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack);
+ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack);
