@@ -153,9 +153,10 @@ __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &t
     s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
 }
 
-// 128-bit streaming accesses, all with the non-temporal hint: every byte is touched once.  Measured
-// on tensors that come from HBM: hinted stores are worth about 5 %, hinted loads another 1-3 %.
-// (On a tensor its producer left in the 256 MB last-level cache the load hint costs about 4 %.)
+// 128-bit streaming accesses: every byte is touched once.  Measured on tensors that come from HBM:
+// loads with the non-temporal hint gain 1-3 % over plain loads (on a tensor its producer left in the
+// 256 MB last-level cache the hint costs about 4 %); stores gain about 5 % from the hint and another
+// 1-2 % from system-scope write-through (sc0 sc1), which the compiler has no builtin for.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint4 load_stream(const uint4 *p)
@@ -165,7 +166,16 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p)
 }
 __device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
 {
-    __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4 *>(p));
+    const u32x4 t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(t) : "memory");
+}
+// One dword at `base` (uniform) + `byte_offset` (per lane).
+__device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offset, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, %2 sc0 sc1 nt"
+                 :
+                 : "v"(byte_offset), "v"(v), "s"(base)
+                 : "memory");
 }
 
 enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
@@ -388,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__res
     at.g = at.f + 4u * H2;
     at.o = at.g + 4u * H2;
 
-    unsigned h_at = 4u * p;  // byte offset of this lane's output word inside one step of h
+    const unsigned h_at = 4u * p;  // byte offset of this lane's output word inside one step of h
 
     GateWords stage[kStages];
 #pragma unroll
@@ -419,12 +429,7 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__res
                 } else {
                     h = lstm_step<false>(q, c.x, c.y, tab);
                 }
-                asm volatile("" : "+v"(h_at));  // same reason as in load_gates
-                if (live) {
-                    uint32_t *h_step = h_out + (unsigned long long)t * n_pairs;
-                    __builtin_nontemporal_store(
-                        h, reinterpret_cast<uint32_t *>(reinterpret_cast<char *>(h_step) + h_at));
-                }
+                if (live) store_stream(h_out + (unsigned long long)t * n_pairs, h_at, h);
             }
         }
     }
