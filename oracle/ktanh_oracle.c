@@ -19,6 +19,12 @@
  *   oracle_klstm_cell      an LSTM cell's gate non-linearities evaluated with
  *                          the above (the GNMT workload of Section 3 motivates
  *                          it; the paper prints no formula for it)
+ *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
+ *                          the 64-interval variant the last paragraph of
+ *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
+ *                          exponent, 4 MSBs of the mantissa); the paper prints
+ *                          no table for it, so its parity is pinned only by an
+ *                          independent brute-force fit and by the invariants
  *
  * Pinned by tests that use no code from here: the fit reproduces Table 1, the
  * closed form of Algorithm 1's affine branch, hand-derived worked values, odd
@@ -92,13 +98,14 @@ void oracle_table1(oracle_lut *lut)
  *     the mean residual, halves rounded up, then clamped to [b_min, b_max];
  *   - r_max = p = 7; the smallest objective wins, the smaller r on a tie.
  */
-void oracle_fit_lut(oracle_lut *lut)
+static void fit_intervals(int s, uint8_t *TE, uint8_t *Tr, int8_t *Tb)
 {
-    const int p = 7, s = 3, q = 7;
-    const int per = 1 << (p - s); /* 16 inputs per interval */
+    const int p = 7, q = 7;
+    const int per = 1 << (p - s); /* inputs per interval: 16 for s = 3, 8 for s = 4 */
+    const int n_intervals = 4 << s;
 
-    for (int t = 0; t < N_INTERVALS; ++t) {
-        int e_low = t >> s;          /* two LSBs of the input exponent */
+    for (int t = 0; t < n_intervals; ++t) {
+        int e_low = t >> s;            /* two LSBs of the input exponent */
         int midx = t & ((1 << s) - 1); /* mantissa_idx_val               */
         /* the exponent field in 125..128 whose two low bits are e_low */
         int e_in = 125 + ((e_low - 125) & 3);
@@ -156,11 +163,22 @@ void oracle_fit_lut(oracle_lut *lut)
             }
             if (cost < best_cost) { best_cost = cost; best_r = r; best_b = (int)b; }
         }
-        lut->E[t] = (uint8_t)bestE;
-        lut->r[t] = (uint8_t)best_r;
-        lut->b[t] = (int8_t)best_b;
+        TE[t] = (uint8_t)bestE;
+        Tr[t] = (uint8_t)best_r;
+        Tb[t] = (int8_t)best_b;
     }
 }
+
+void oracle_fit_lut(oracle_lut *lut) { fit_intervals(3, lut->E, lut->r, lut->b); }
+
+/* The 64-interval variant: 4 mantissa MSBs in the index, 8 inputs per interval. */
+typedef struct {
+    uint8_t E[64];
+    uint8_t r[64];
+    int8_t b[64];
+} oracle_lut64;
+
+void oracle_fit_lut64(oracle_lut64 *lut) { fit_intervals(4, lut->E, lut->r, lut->b); }
 
 /* ------------------------------------------------------------------ */
 /* Algorithm 1 on one BFloat16 bit pattern (s:1, E:8, M:7).
@@ -174,7 +192,8 @@ void oracle_fit_lut(oracle_lut *lut)
  * and +-Inf saturates.  A NaN (exponent all ones, mantissa non-zero) is not a
  * magnitude: it is returned with its quiet bit set, sign and payload kept.
  */
-static uint16_t ktanh_bf16_scalar(uint16_t x, const oracle_lut *lut)
+static uint16_t ktanh_bf16_fields(uint16_t x, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                  const int8_t *Tb)
 {
     const unsigned p = 7;
     unsigned s_i = (x >> 15) & 1u;
@@ -193,18 +212,24 @@ static uint16_t ktanh_bf16_scalar(uint16_t x, const oracle_lut *lut)
     } else if (cond > cond_T2) {
         s_o = s_i; E_o = 127u; M_o = 0u;
     } else {
-        unsigned t = ((E_i & 3u) << 3) | (M_i >> (p - 3));
-        int Mo = (int)(M_i >> lut->r[t]) + (int)lut->b[t];
-        s_o = s_i; E_o = lut->E[t]; M_o = (unsigned)Mo & 0x7Fu;
+        unsigned t = ((E_i & 3u) << s) | (M_i >> (p - s)); /* s = 3: Table 1's index */
+        int Mo = (int)(M_i >> Tr[t]) + (int)Tb[t];
+        s_o = s_i; E_o = TE[t]; M_o = (unsigned)Mo & 0x7Fu;
     }
     return (uint16_t)((s_o << 15) | (E_o << p) | M_o);
+}
+
+static uint16_t ktanh_bf16_scalar(uint16_t x, const oracle_lut *lut)
+{
+    return ktanh_bf16_fields(x, 3, lut->E, lut->r, lut->b);
 }
 
 /* Algorithm 1 on one Float32 bit pattern (s:1, E:8, M:23).  The paper fits
  * BFloat16 only; here its 8-bit parameters act on the 23-bit mantissa with the
  * offset aligned to the mantissa's leading 7 bits: M_o = (M >> r) + b * 2^16.
  * Same thresholds, same interval index. */
-static uint32_t ktanh_f32_scalar(uint32_t x, const oracle_lut *lut)
+static uint32_t ktanh_f32_fields(uint32_t x, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                 const int8_t *Tb)
 {
     const unsigned p = 23;
     uint32_t s_i = (x >> 31) & 1u;
@@ -223,11 +248,16 @@ static uint32_t ktanh_f32_scalar(uint32_t x, const oracle_lut *lut)
     } else if (cond > cond_T2) {
         s_o = s_i; E_o = 127u; M_o = 0u;
     } else {
-        uint32_t t = ((E_i & 3u) << 3) | (M_i >> (p - 3));
-        int64_t Mo = (int64_t)(M_i >> lut->r[t]) + (int64_t)lut->b[t] * 65536;
-        s_o = s_i; E_o = lut->E[t]; M_o = (uint32_t)Mo & 0x7FFFFFu;
+        uint32_t t = ((E_i & 3u) << s) | (M_i >> (p - s));
+        int64_t Mo = (int64_t)(M_i >> Tr[t]) + (int64_t)Tb[t] * 65536;
+        s_o = s_i; E_o = TE[t]; M_o = (uint32_t)Mo & 0x7FFFFFu;
     }
     return (s_o << 31) | (E_o << p) | M_o;
+}
+
+static uint32_t ktanh_f32_scalar(uint32_t x, const oracle_lut *lut)
+{
+    return ktanh_f32_fields(x, 3, lut->E, lut->r, lut->b);
 }
 
 /* ------------------------------------------------------------------ */
@@ -268,6 +298,17 @@ void oracle_ktanh_bf16(const uint16_t *in, uint16_t *out, size_t n, const oracle
 void oracle_ktanh_f32(const uint32_t *in, uint32_t *out, size_t n, const oracle_lut *lut)
 {
     for (size_t i = 0; i < n; ++i) out[i] = ktanh_f32_scalar(in[i], lut);
+}
+
+/* Algorithm 1 with the 64-interval tables (index = 2 LSBs of E_i, 4 MSBs of M_i). */
+void oracle_ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ktanh_bf16_fields(in[i], 4, lut->E, lut->r, lut->b);
+}
+
+void oracle_ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ktanh_f32_fields(in[i], 4, lut->E, lut->r, lut->b);
 }
 
 void oracle_ksigmoid(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut)

@@ -40,19 +40,21 @@ def test_fit_regenerates_table1(oracle):
     assert oracle.fit_lut().as_tuples() == _table1_from_text()
 
 
-def test_table1_is_the_brute_force_argmin_of_eq1():
-    """Independent of the C fit: enumerate every (r, b) in range and score eq. (1) in numpy."""
-    tab = _table1_from_text()
-    p, s = 7, 3
-    for t in range(32):
-        e_in = {1: 125, 2: 126, 3: 127, 0: 128}[t >> 3]
-        j = t & 7
-        m = np.arange(j * 16, j * 16 + 16, dtype=np.float64)
+def _brute_force_fit(s):
+    """Section 2.4 in numpy, independent of the C fit: Step 2 as written, Step 3 by enumerating
+    every (r, b) inside the b_min / b_max bounds and scoring eq. (1).  Returns the table and the
+    smallest ratio runner-up / winner of the Step 3 objective (how far from a tie the fit is)."""
+    p = 7
+    per = 1 << (p - s)
+    table, margin = [], np.inf
+    for t in range(4 << s):
+        e_in = {1: 125, 2: 126, 3: 127, 0: 128}[t >> s]
+        j = t & ((1 << s) - 1)
+        m = np.arange(j * per, (j + 1) * per, dtype=np.float64)
         y = np.tanh(np.ldexp(1.0 + m / 128.0, e_in - 127))
         fr, ex = np.frexp(y)
         Ei = ex - 1 + 127
         Mi = (2.0 * fr - 1.0) * 128.0
-        # Step 2
         best = None
         for E in sorted(set(Ei.tolist())):
             Mh = np.where(Ei == E, Mi, np.where(E > Ei, 0.0, 127.0))
@@ -60,16 +62,30 @@ def test_table1_is_the_brute_force_argmin_of_eq1():
             if best is None or cost < best[0]:
                 best = (cost, E, Mh)
         _, E, Mh = best
-        # Step 3 by exhaustive search under the b_min / b_max bounds
-        arg, arg_cost = None, np.inf
+        scored = []
         for r in range(0, p + 1):
             bmax = 2 ** p - 1 - (((j + 1) * 2 ** (p - s) - 1) >> r)
             bmin = -j * (2 ** (p - s - r) if p - s - r >= 0 else 0)
             for b in range(bmin, bmax + 1):
-                cost = np.sum((Mh - (m / 2.0 ** r + b)) ** 2)
-                if cost < arg_cost:
-                    arg, arg_cost = (r, b), cost
-        assert (E, arg[0], arg[1]) == tab[t], f"interval {t:05b}"
+                scored.append((np.sum((Mh - (m / 2.0 ** r + b)) ** 2), r, b))
+        scored.sort()
+        table.append((E, scored[0][1], scored[0][2]))
+        margin = min(margin, scored[1][0] / scored[0][0])
+    return table, margin
+
+
+def test_table1_is_the_brute_force_argmin_of_eq1():
+    table, margin = _brute_force_fit(3)
+    assert table == _table1_from_text()
+    assert margin > 1.01          # no interval is anywhere near a tie
+
+
+def test_fit64_is_the_brute_force_argmin_of_eq1(oracle):
+    """The paper prints no 64-interval table; the oracle's fit is held against the exhaustive
+    search instead."""
+    table, margin = _brute_force_fit(4)
+    assert oracle.fit_lut64().as_tuples() == table
+    assert margin > 1.001
 
 
 def test_table1_respects_overflow_bounds():
@@ -362,3 +378,46 @@ def test_a_wrong_table_entry_is_caught_by_the_error_or_fit_pins(oracle, t, field
     assert oracle.OracleLut.from_tuples(rows).as_tuples() != _table1_from_text()
     x = wl.all_bf16_patterns()
     assert not np.array_equal(oracle.ktanh_bf16(x, oracle.OracleLut.from_tuples(rows)), oracle.ktanh_bf16(x))
+
+
+# ---------------------------------------------------------------- 64-interval variant
+def test_ktanh64_invariants_and_error(oracle):
+    """Same algorithm, 6-bit index (Section 2.4, last paragraph).  No printed values exist; what
+    is fixed: the closed form from the brute-force table, symmetry, regions, range, Table 2's
+    bound, and a smaller relative error than with 32 intervals."""
+    table, _ = _brute_force_fit(4)
+    lut64 = oracle.OracleLut64.from_tuples(table)
+    x = wl.all_bf16_patterns()
+    y = oracle.ktanh64_bf16(x, lut64)
+    assert np.array_equal(oracle.ktanh64_bf16(x ^ 0x8000, lut64), y ^ 0x8000)
+    mag, sign = x & 0x7FFF, x & 0x8000
+    small, big, nan = mag < 0x3E80, (mag >= 0x4080) & (mag <= 0x7F80), mag > 0x7F80
+    assert np.array_equal(y[small], x[small]) and np.array_equal(y[big], sign[big] | 0x3F80)
+    assert np.array_equal(y[nan], x[nan] | 0x0040)
+    mid = ~(small | big | nan)
+    xs = x[mid].astype(np.int64)
+    E, M = (xs >> 7) & 0xFF, xs & 0x7F
+    t = ((E & 3) << 4) | (M >> 3)
+    Et, rt, bt = (np.array([table[k][c] for k in t]) for c in range(3))
+    mo = (M >> rt) + bt
+    assert mo.min() >= 0 and mo.max() <= 127
+    expect = np.ldexp(1.0 + mo / 128.0, Et - 127) * np.where(xs & 0x8000, -1.0, 1.0)
+    assert np.array_equal(_bf16_val(y[mid]), expect)
+    fin = mag < 0x7F80
+    ref = np.tanh(_bf16_val(x[fin]))
+    err64 = np.abs(_bf16_val(y[fin]) - ref)
+    err32 = np.abs(_bf16_val(oracle.ktanh_bf16(x)[fin]) - ref)
+    nz = ref != 0
+    assert err64.max() <= 1.67e-2
+    assert (err64[nz] / np.abs(ref[nz])).max() < (err32[nz] / np.abs(ref[nz])).max() <= 3.03e-2
+    region = (np.abs(_bf16_val(x[fin])) >= 0.25) & (np.abs(_bf16_val(x[fin])) < 4)
+    assert err64[region].mean() < err32[region].mean()
+
+
+def test_ktanh64_f32_truncation_invariant(oracle):
+    u = _f32_probe_patterns()
+    y = oracle.ktanh64_f32(u)
+    notnan = (u & 0x7FFFFFFF) <= 0x7F800000
+    assert np.array_equal((y >> 16).astype(np.uint16)[notnan], oracle.ktanh64_bf16((u >> 16).astype(np.uint16))[notnan])
+    assert np.array_equal(y[~notnan], u[~notnan] | 0x00400000)
+    assert np.array_equal(oracle.ktanh64_f32(u ^ 0x80000000), y ^ 0x80000000)
