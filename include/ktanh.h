@@ -99,6 +99,36 @@ ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n, const ktanh_l
 ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
                      ktanh_stream_t stream);
 
+/* ---- 64-interval variant ------------------------------------------------------------------------
+ * Section 2.4 (last paragraph): the parameters are 8-bit, so 64 intervals fit where AVX512 held 32
+ * 16-bit values.  Index t = (2 LSBs of E_i) << 4 | (4 MSBs of M_i); t = 16..31 covers [0.25, 0.5),
+ * 32..47 [0.5, 1), 48..63 [1, 2), 0..15 [2, 4).  Thresholds and everything else as in Algorithm 1. */
+#define KTANH_INTERVALS64 64
+
+typedef struct ktanh_lut64 {
+    uint8_t E[KTANH_INTERVALS64];
+    uint8_t r[KTANH_INTERVALS64];
+    int8_t  b[KTANH_INTERVALS64];
+} ktanh_lut64_t;
+
+/* Offline parameter fit of Section 2.4 (Steps 1-3: common output exponent per interval, then the
+ * (r, b) that minimise eq. (1) under the overflow bounds b_min, b_max of eq. (2)), for BFloat16
+ * inputs.  Host-only, double precision, microseconds; `out` is a host pointer the caller owns.
+ * ktanh_fit_lut reproduces Table 1; ktanh_fit_lut64 produces the 64-interval tables.
+ * Returns KT_OK or KT_ERR_NULL. */
+ktanh_status_t ktanh_fit_lut(ktanh_lut_t *out);
+ktanh_status_t ktanh_fit_lut64(ktanh_lut64_t *out);
+
+/* Same check as ktanh_lut_validate for a 64-interval table (8 mantissas per interval). */
+ktanh_status_t ktanh_lut64_validate(const ktanh_lut64_t *lut);
+
+/* K-TanH with a 64-interval table on BFloat16 / Float32: same contract as ktanh_bf16 / ktanh_f32.
+ * `lut` == NULL selects the table ktanh_fit_lut64 produces (fitted once per process, on first use). */
+ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
+                            ktanh_stream_t stream);
+ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n, const ktanh_lut64_t *lut,
+                           ktanh_stream_t stream);
+
 /* Element-wise part of an LSTM cell with K-TanH non-linearities (the recurrent GNMT workload of
  * Section 3 is what it serves; Sigmoid as in Section 1), over T consecutive time steps whose gate
  * pre-activations are all given:

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libktanh.so")
 INTERVALS = 32
 
 EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "ktanh_bf16",
-           "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell")
+           "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell",
+           "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32")
 
 
 class KtanhLut(ctypes.Structure):
@@ -38,6 +39,26 @@ class KtanhLut(ctypes.Structure):
 
     def as_tuples(self):
         return [(int(self.E[t]), int(self.r[t]), int(self.b[t])) for t in range(INTERVALS)]
+
+
+class KtanhLut64(ctypes.Structure):
+    """Mirror of ``ktanh_lut64_t``: 64-interval tables, t = (E_i & 3) << 4 | (M_i >> 3)."""
+
+    _fields_ = [
+        ("E", ctypes.c_uint8 * 64),
+        ("r", ctypes.c_uint8 * 64),
+        ("b", ctypes.c_int8 * 64),
+    ]
+
+    @classmethod
+    def from_tuples(cls, rows):
+        lut = cls()
+        for t, (E, r, b) in enumerate(rows):
+            lut.E[t], lut.r[t], lut.b[t] = E, r, b
+        return lut
+
+    def as_tuples(self):
+        return [(int(self.E[t]), int(self.r[t]), int(self.b[t])) for t in range(64)]
 
 
 class KtanhError(RuntimeError):
@@ -70,6 +91,17 @@ def load_library() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         lib.klstm_cell.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp, vp]
         lib.klstm_cell.restype = ctypes.c_int
+        lp64 = ctypes.POINTER(KtanhLut64)
+        lib.ktanh_fit_lut.argtypes = [lp]
+        lib.ktanh_fit_lut.restype = ctypes.c_int
+        lib.ktanh_fit_lut64.argtypes = [lp64]
+        lib.ktanh_fit_lut64.restype = ctypes.c_int
+        lib.ktanh_lut64_validate.argtypes = [lp64]
+        lib.ktanh_lut64_validate.restype = ctypes.c_int
+        for name in ("ktanh64_bf16", "ktanh64_f32"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, sz, lp64, vp]
+            fn.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -88,6 +120,28 @@ def ktanh_default_lut() -> KtanhLut:
 
 def ktanh_lut_validate(lut: KtanhLut | None) -> int:
     return load_library().ktanh_lut_validate(ctypes.byref(lut) if lut is not None else None)
+
+
+def ktanh_fit_lut() -> KtanhLut:
+    """The 32-interval table from the library's own fit of Section 2.4 (equals Table 1)."""
+    lut = KtanhLut()
+    st = load_library().ktanh_fit_lut(ctypes.byref(lut))
+    if st != 0:
+        raise KtanhError(st, "ktanh_fit_lut")
+    return lut
+
+
+def ktanh_fit_lut64() -> KtanhLut64:
+    """The 64-interval table from the library's fit."""
+    lut = KtanhLut64()
+    st = load_library().ktanh_fit_lut64(ctypes.byref(lut))
+    if st != 0:
+        raise KtanhError(st, "ktanh_fit_lut64")
+    return lut
+
+
+def ktanh_lut64_validate(lut: KtanhLut64 | None) -> int:
+    return load_library().ktanh_lut64_validate(ctypes.byref(lut) if lut is not None else None)
 
 
 def _stream_handle(stream):
@@ -134,6 +188,16 @@ def ktanh_bf16(x, out=None, lut=None, stream=None):
 def ktanh_f32(x, out=None, lut=None, stream=None):
     """K-TanH on a Float32 tensor (or its int32/uint32 bit view)."""
     return _elementwise("ktanh_f32", x, out, lut, stream, _F32_VIEWS)
+
+
+def ktanh64_bf16(x, out=None, lut=None, stream=None):
+    """K-TanH with a 64-interval table (``KtanhLut64``; None = the fitted one) on BFloat16."""
+    return _elementwise("ktanh64_bf16", x, out, lut, stream, _BF16_VIEWS)
+
+
+def ktanh64_f32(x, out=None, lut=None, stream=None):
+    """K-TanH with a 64-interval table on Float32."""
+    return _elementwise("ktanh64_f32", x, out, lut, stream, _F32_VIEWS)
 
 
 def ksigmoid(x, out=None, lut=None, stream=None):

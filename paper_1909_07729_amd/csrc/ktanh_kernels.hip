@@ -82,6 +82,20 @@ __device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTabl
     return bitsel(pass, mag2, lut2);
 }
 
+// The same with a 64-interval table (index = 2 low exponent bits, 4 high mantissa bits): all 64
+// lanes hold table entries, so saturation is a select of its own.
+__device__ __forceinline__ uint32_t ktanh64_mag_pair(uint32_t mag2, const LaneTable &tab)
+{
+    const uint32_t e_lo = tab.get(mag2 >> 1);   // bits [7:2] <- bits [8:3] of the low value
+    const uint32_t e_hi = tab.get(mag2 >> 17);  // same bits of the high value
+    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
+    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mag2) >> as_u16x2(r2)));
+    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    const uint32_t beyond = sign_mask_pair(as_u32(as_i16x2(0x407F407Fu) - as_i16x2(mag2)));
+    return bitsel(beyond, 0x3F803F80u, bitsel(pass, mag2, lut2));
+}
+
 // 0xFFFF in each half that holds a NaN magnitude (> 0x7F80).
 __device__ __forceinline__ uint32_t nan_mask_pair(uint32_t mag2)
 {
@@ -90,11 +104,12 @@ __device__ __forceinline__ uint32_t nan_mask_pair(uint32_t mag2)
 
 // K-TanH of two BFloat16 values, signs included.  NANS = false leaves out the NaN rule (a NaN then
 // comes out as +-1): for callers that have already established that no NaN can reach this point.
-template <bool NANS = true>
+template <bool NANS = true, bool WIDE = false>
 __device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
 {
     const uint32_t mag2 = w & kMag2;
-    const uint32_t res = bitsel(kMag2, ktanh_mag_pair(mag2, tab), w);
+    const uint32_t res =
+        bitsel(kMag2, WIDE ? ktanh64_mag_pair(mag2, tab) : ktanh_mag_pair(mag2, tab), w);
     if constexpr (!NANS) return res;
     return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
 }
@@ -111,13 +126,16 @@ __device__ __forceinline__ uint32_t max_pair(uint32_t a2, uint32_t b2)
 
 // Algorithm 1 on one Float32 pattern: same slot from the same leading bits; the 8-bit parameters
 // act on the 23-bit mantissa, b_t aligned to its top seven bits.
+template <bool WIDE = false>
 __device__ __forceinline__ uint32_t ktanh_f32_one(uint32_t u, const LaneTable &tab)
 {
     const uint32_t mag = u & 0x7FFFFFFFu;
     const uint32_t mc = mag < 0x40800000u ? mag : 0x40800000u;
-    const uint32_t e = tab.get(mc >> 18);  // bits [7:2] <- bits [25:20]
-    // Float32 slots (kt_pack_lut_f32) keep the plain base (E_t << 7) + b_t in the high half.
-    const uint32_t lut = (e & 0xFFFF0000u) + ((mc & 0x007FFFFFu) >> (e & 31u));
+    // 32 intervals: bits [7:2] <- bits [25:20] (slot 8 = saturation); 64 intervals: <- bits [24:19]
+    const uint32_t e = tab.get(WIDE ? mag >> 17 : mc >> 18);
+    // Float32 slots (kt_pack_lut*_f32) keep the plain base (E_t << 7) + b_t in the high half.
+    uint32_t lut = (e & 0xFFFF0000u) + ((mc & 0x007FFFFFu) >> (e & 31u));
+    if constexpr (WIDE) lut = mag < 0x40800000u ? lut : 0x3F800000u;
     uint32_t res = mag < 0x3E800000u ? mag : lut;
     res = mag > 0x7F800000u ? (mag | 0x00400000u) : res;
     return res | (u & 0x80000000u);
@@ -178,13 +196,15 @@ __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offse
                  : "memory");
 }
 
-enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_TANH64 = 4 };
 
 template <int OP>
 __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
 {
     if constexpr (OP == OP_TANH) {
         return ktanh_pair(w, tab);
+    } else if constexpr (OP == OP_TANH64) {
+        return ktanh_pair<true, true>(w, tab);
     } else if constexpr (OP == OP_SIGMOID) {
         float s_lo, s_hi;
         ksigmoid_f32_pair(w, tab, s_lo, s_hi);
@@ -215,10 +235,11 @@ __device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
                  apply_pair<OP>(v.w, tab)};
 }
 
+template <bool WIDE>
 __device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
 {
-    return uint4{ktanh_f32_one(v.x, tab), ktanh_f32_one(v.y, tab), ktanh_f32_one(v.z, tab),
-                 ktanh_f32_one(v.w, tab)};
+    return uint4{ktanh_f32_one<WIDE>(v.x, tab), ktanh_f32_one<WIDE>(v.y, tab),
+                 ktanh_f32_one<WIDE>(v.z, tab), ktanh_f32_one<WIDE>(v.w, tab)};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -238,7 +259,7 @@ struct EdgeArgs {
 template <bool F32, int OP>
 __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
 {
-    if constexpr (F32) return apply_vec_f32(v, tab);
+    if constexpr (F32) return apply_vec_f32<OP == OP_TANH64>(v, tab);
     else return apply_vec_bf16<OP>(v, tab);
 }
 
@@ -276,7 +297,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
-            x = ktanh_f32_one(x, tab);
+            x = ktanh_f32_one<OP == OP_TANH64>(x, tab);
             if (live) static_cast<uint32_t *>(edge.eout)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(edge.ein)[i];
@@ -301,7 +322,7 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(in)[i];
-            x = ktanh_f32_one(x, tab);
+            x = ktanh_f32_one<OP == OP_TANH64>(x, tab);
             if (live) static_cast<uint32_t *>(out)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(in)[i];
@@ -454,8 +475,17 @@ int compute_units()
 
 constexpr unsigned kBlocksPerCu = 8;  // resident blocks per compute unit the grid is sized for
 
-template <bool F32, int OP>
-ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const ktanh_lut_t *lut,
+ktanh_status_t pack_for(const ktanh_lut_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut_f32(lut, pack) : kt_pack_lut_bf16(lut, pack);
+}
+ktanh_status_t pack_for(const ktanh_lut64_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
+}
+
+template <bool F32, int OP, class Lut>
+ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut *lut,
                                   ktanh_stream_t stream)
 {
     constexpr size_t kElem = F32 ? 4 : 2;
@@ -466,7 +496,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
     if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
     if (n > (size_t)1 << 40) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
     KtLutPack pack;
-    const ktanh_status_t st = F32 ? kt_pack_lut_f32(lut, &pack) : kt_pack_lut_bf16(lut, &pack);
+    const ktanh_status_t st = pack_for(lut, F32, &pack);
     if (st != KT_OK) return st;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -485,7 +515,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const kta
         edge.n_edge = (unsigned)(head + tail);
         const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
         uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
-        constexpr int kUnroll = (F32 || OP == OP_TANH) ? 1 : 2;
+        constexpr int kUnroll = (F32 || OP == OP_TANH || OP == OP_TANH64) ? 1 : 2;
         size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
@@ -512,6 +542,18 @@ extern "C" ktanh_status_t ktanh_f32(const uint32_t *in, uint32_t *out, size_t n,
                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
 {
     return launch_elementwise<true, OP_TANH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n,
+                                       const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TANH64>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n,
+                                      const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_TANH64>(in, out, n, lut, stream);
 }
 
 extern "C" ktanh_status_t ksigmoid(const uint16_t *in, uint16_t *out, size_t n,

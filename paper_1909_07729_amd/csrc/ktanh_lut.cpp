@@ -89,3 +89,56 @@ ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack)
 {
     return pack_slots(lut, pack, false);
 }
+
+// ---- 64-interval variant ------------------------------------------------------------------------
+extern "C" ktanh_status_t ktanh_lut64_validate(const ktanh_lut64_t *lut)
+{
+    if (lut == nullptr) return KT_ERR_NULL;
+    for (int t = 0; t < KTANH_INTERVALS64; ++t) {
+        const int E = lut->E[t], r = lut->r[t], b = lut->b[t];
+        if (E < 1 || E > 254 || r > 7) return KT_ERR_LUT;
+        const int m_first = (t & 15) << 3, m_last = m_first + 7;
+        if ((m_first >> r) + b < 0 || (m_last >> r) + b > 127) return KT_ERR_LUT;
+    }
+    return KT_OK;
+}
+
+namespace {
+
+const ktanh_lut64_t *fitted_lut64()
+{
+    static const ktanh_lut64_t fitted = [] {
+        ktanh_lut64_t t;
+        ktanh_fit_lut64(&t);
+        return t;
+    }();
+    return &fitted;
+}
+
+ktanh_status_t pack_slots64(const ktanh_lut64_t *lut, KtLutPack *pack, bool fold_input_exponent)
+{
+    if (lut == nullptr) lut = fitted_lut64();
+    const ktanh_status_t st = ktanh_lut64_validate(lut);
+    if (st != KT_OK) return st;
+    for (int t = 0; t < KTANH_INTERVALS64; ++t) {
+        const int r = lut->r[t];
+        // the input exponent in 125..128 whose two low bits are t >> 4
+        const int e_in = 125 + ((((t >> 4) & 3) - 125) & 3);
+        int base = (lut->E[t] << 7) + lut->b[t];
+        if (fold_input_exponent) base -= e_in << (7 - r);
+        pack->slot[t] = ((uint32_t)(base & 0xFFFF) << 16) | (uint32_t)r;
+    }
+    return KT_OK;
+}
+
+}  // namespace
+
+ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack)
+{
+    return pack_slots64(lut, pack, true);
+}
+
+ktanh_status_t kt_pack_lut64_f32(const ktanh_lut64_t *lut, KtLutPack *pack)
+{
+    return pack_slots64(lut, pack, false);
+}

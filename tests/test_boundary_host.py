@@ -88,3 +88,41 @@ def test_binding_refuses_host_tensors(binding):
     import torch
     with pytest.raises(ValueError):
         binding.ktanh_bf16(torch.zeros(8, dtype=torch.bfloat16))
+
+
+def test_library_fit_reproduces_table1_and_matches_the_oracle_fit64(binding, oracle):
+    """The library carries its own implementation of Section 2.4's optimisation (no code shared with
+    the oracle): 32 intervals must give Table 1, 64 intervals what the oracle's fit gives."""
+    want = [None] * 32
+    for bits, E, r, b in read_golden("table1_bf16.txt"):
+        want[int(bits, 2)] = (int(E), int(r), int(b))
+    assert binding.ktanh_fit_lut().as_tuples() == want
+    lut64 = binding.ktanh_fit_lut64()
+    assert lut64.as_tuples() == oracle.fit_lut64().as_tuples()
+    assert binding.ktanh_lut64_validate(lut64) == 0
+    lib = binding.load_library()
+    assert lib.ktanh_fit_lut(None) == 1 and lib.ktanh_fit_lut64(None) == 1
+
+
+def test_lut64_validation(binding):
+    assert binding.ktanh_lut64_validate(None) == 1
+    rows = binding.ktanh_fit_lut64().as_tuples()
+
+    def status(t, row):
+        bad = list(rows); bad[t] = row
+        return binding.ktanh_lut64_validate(binding.KtanhLut64.from_tuples(bad))
+
+    assert status(15, (126, 6, 126)) == 0         # (127 >> 6) + 126 = 127: the last value allowed
+    assert status(15, (126, 6, 127)) == 3
+    assert status(17, (125, 0, -8)) == 0          # interval 17 starts at mantissa 8
+    assert status(17, (125, 0, -9)) == 3
+    assert status(40, (126, 8, 0)) == 3 and status(40, (0, 1, 0)) == 3
+    lib = binding.load_library()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    bad = binding.KtanhLut64.from_tuples([(126, 9, 0)] * 64)
+    for name in ("ktanh64_bf16", "ktanh64_f32"):
+        fn = getattr(lib, name)
+        assert fn(null, null, 0, None, null) == 0
+        assert fn(null, fake, 8, None, null) == 1
+        assert fn(ctypes.c_void_p(0x1001), fake, 8, None, null) == 2
+        assert fn(fake, fake, 8, ctypes.byref(bad), null) == 3

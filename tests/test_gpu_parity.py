@@ -250,3 +250,35 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
         _assert_bf16_equal(_to_host(sd, np.uint16), want_s, False, f"kgelu replay {replay}")
         assert np.array_equal(cw.cpu().numpy(), want_c), f"replay {replay}"
         assert np.array_equal(_to_host(hd, np.uint16), want_h), f"replay {replay}"
+
+
+# ------------------------------------------------------------------ 64-interval variant
+def test_ktanh64_exhaustive_ragged_and_custom_table(gpu, oracle):
+    binding, torch = gpu
+    x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(100003, seed=64)])
+    got = _to_host(binding.ktanh64_bf16(_to_dev(torch, x)), np.uint16)
+    assert np.array_equal(got, oracle.ktanh64_bf16(x))
+    rows = oracle.fit_lut64().as_tuples()
+    rows[48] = (126, 0, 60); rows[17] = (125, 1, 4); rows[15] = (127, 7, 0); rows[32] = (124, 3, 100)
+    got = _to_host(binding.ktanh64_bf16(_to_dev(torch, x), lut=binding.KtanhLut64.from_tuples(rows)), np.uint16)
+    assert np.array_equal(got, oracle.ktanh64_bf16(x, oracle.OracleLut64.from_tuples(rows)))
+    xd = _to_dev(torch, x)
+    outd = torch.full((x.size + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    binding.ktanh64_bf16(xd[3:], out=outd[5:5 + x.size - 3])          # element-wise fallback path
+    res = _to_host(outd, np.uint16)
+    assert np.array_equal(res[5:5 + x.size - 3], oracle.ktanh64_bf16(x[3:]))
+    assert np.all(res[:5] == 0x5A5A) and np.all(res[5 + x.size - 3:] == 0x5A5A)
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    u = np.concatenate([hi, hi | 0xFFFF, hi | 0x8000, wl.f32_mixture((1 << 20) + 5, seed=65)])
+    got = _to_host(binding.ktanh64_f32(_to_dev(torch, u)), np.uint32)
+    assert np.array_equal(got, oracle.ktanh64_f32(u))
+
+
+def test_ktanh64_full_size(gpu, oracle):
+    binding, torch = gpu
+    x = wl.lstm_gate_preactivations()
+    got = _to_host(binding.ktanh64_bf16(_to_dev(torch, x)), np.uint16)
+    assert np.array_equal(got, oracle.ktanh64_bf16(x))
+    u = wl.f32_mixture(1 << 26)
+    got = _to_host(binding.ktanh64_f32(_to_dev(torch, u)), np.uint32)
+    assert np.array_equal(got, oracle.ktanh64_f32(u))
