@@ -23,8 +23,9 @@
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
  *                          exponent, 4 MSBs of the mantissa); the paper prints
- *                          no table for it, so its parity is pinned only by an
- *                          independent brute-force fit and by the invariants
+ *                          no table for it (parity unpinned by printed
+ *                          values): it is pinned by an independent brute-force
+ *                          fit and by the invariants
  *
  * Pinned by tests that use no code from here: the fit reproduces Table 1, the
  * closed form of Algorithm 1's affine branch, hand-derived worked values, odd
