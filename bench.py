@@ -173,6 +173,9 @@ def run_extras(torch, binding, wl, upload, xs, ys):
     record("ktanh_bf16_cache_resident", "[50,128,4096] bf16, one buffer pair reused (fits the 256 MB cache)",
            lambda i: binding.ktanh_bf16(xs[0], out=ys[0]), xs[0].numel(), 4, 500)
 
+    # yardstick: the runtime's own device-to-device copy of the same tensor (same bytes, no arithmetic)
+    record("plain_copy_same_size", "hipMemcpyAsync device-to-device of the headline tensor, same 8 rotating pairs",
+           lambda i: ys[i % ROTATE].copy_(xs[i % ROTATE]), xs[0].numel(), 4, 1000, 20)
     record("ktanh64_bf16", "[50,128,4096] bf16 as in the headline, 64-interval table, 8 rotating buffer pairs",
            lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 1000, 20)
 

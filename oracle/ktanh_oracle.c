@@ -19,6 +19,16 @@
  *   oracle_klstm_cell      an LSTM cell's gate non-linearities evaluated with
  *                          the above (the GNMT workload of Section 3 motivates
  *                          it; the paper prints no formula for it)
+ *   oracle_ktanh_f32_to_bf16
+ *                          K-TanH on BFloat16 inputs that arrive as Float32:
+ *                          the Float32 -> BFloat16 conversion that Section 2.5
+ *                          leaves out of its cycle count, then Algorithm 1
+ *   oracle_ksigmoid_f32/kswish_f32/kgelu_f32
+ *                          the Section 1 identities on Float32 tensors with
+ *                          the Float32 form of Algorithm 1 inside (the paper
+ *                          prints nothing for these: pinned through the
+ *                          BFloat16 operations where the two must coincide,
+ *                          and by double-precision re-evaluation)
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
@@ -378,4 +388,55 @@ void oracle_klstm_cell(const uint16_t *gates, const float *c_in, float *c_out, u
             c_out[bi * H + j] = c;
         }
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Float32 tensors.  Same identities, same operation order, Algorithm 1 in its
+ * Float32 form: nothing is rounded to BFloat16 on the way. */
+static float f32_of_bits(uint32_t u) { float f; memcpy(&f, &u, sizeof f); return f; }
+static uint32_t bits_of_f32(float f) { uint32_t u; memcpy(&u, &f, sizeof u); return u; }
+
+static float ksigmoid_f32_scalar(float x, const oracle_lut *lut)
+{
+    float half_x = 0.5f * x;
+    float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(half_x), lut));
+    float half_th = 0.5f * th;
+    return half_th + 0.5f;
+}
+
+void oracle_ksigmoid_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ksigmoid_f32_scalar(in[i], lut);
+}
+
+void oracle_kswish_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float sg = ksigmoid_f32_scalar(in[i], lut);
+        out[i] = in[i] * sg;
+    }
+}
+
+void oracle_kgelu_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
+{
+    const float a = 0.044715f;
+    const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
+    for (size_t i = 0; i < n; ++i) {
+        float x = in[i];
+        float x2 = x * x;
+        float x3 = x2 * x;
+        float ax3 = a * x3;
+        float inner = x + ax3;
+        float arg = c * inner;
+        float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(arg), lut));
+        float half_x = 0.5f * x;
+        float one_plus = 1.0f + th;
+        out[i] = half_x * one_plus;
+    }
+}
+
+/* Float32 in, BFloat16 out: round to nearest even, then Algorithm 1 on BFloat16. */
+void oracle_ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n, const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ktanh_bf16_scalar(narrow_rne(in[i]), lut);
 }

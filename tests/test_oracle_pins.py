@@ -421,3 +421,61 @@ def test_ktanh64_f32_truncation_invariant(oracle):
     assert np.array_equal((y >> 16).astype(np.uint16)[notnan], oracle.ktanh64_bf16((u >> 16).astype(np.uint16))[notnan])
     assert np.array_equal(y[~notnan], u[~notnan] | 0x00400000)
     assert np.array_equal(oracle.ktanh64_f32(u ^ 0x80000000), y ^ 0x80000000)
+
+
+# ---------------------------------------------------------------- Float32 tensors
+def test_f32_sigmoid_and_swish_coincide_with_the_bf16_operations(oracle):
+    """On a BFloat16-representable input whose half is representable too, and whose Float32 K-TanH
+    keeps its low 16 bits zero (no mantissa bit shifted below the BFloat16 grid), the Float32 Sigmoid
+    takes exactly the steps of the BFloat16 one, so rounding its result must give the BFloat16
+    operation's result.  That is the case for about 99 % of the 65,536 inputs."""
+    x = wl.all_bf16_patterns()
+    xf = wl.bf16_bits_to_f32(x)
+    nan = (x & 0x7FFF) > 0x7F80
+    with np.errstate(invalid="ignore"):
+        half = (np.float32(0.5) * xf).view(np.uint32)
+    aligned = ((half & 0xFFFF) == 0) & ((oracle.ktanh_f32(half) & 0xFFFF) == 0)
+    assert aligned.mean() > 0.98
+    for name in ("ksigmoid", "kswish"):
+        with np.errstate(invalid="ignore"):
+            wide = getattr(oracle, name + "_f32")(xf)
+        want = getattr(oracle, name)(x)
+        ok = ~nan & ~np.isnan(wide) & aligned
+        assert np.array_equal(np.isnan(wide), (want & 0x7FFF) > 0x7F80)
+        assert np.array_equal(wl.f32_to_bf16_bits(wide[ok]), want[ok]), name
+    assert oracle.ksigmoid_f32(np.float32([1.0]))[0] == np.float32(0.734375)     # as worked for bf16
+    assert oracle.kswish_f32(np.float32([-8.0])).view(np.uint32)[0] == 0x80000000
+
+
+def test_f32_derived_match_double_recomputation(oracle):
+    xf = wl.f32_mixture(1 << 18, seed=5).view(np.float32)
+    x64 = xf.astype(np.float64)
+    K = lambda v: oracle.ktanh_f32(v.astype(np.float32).view(np.uint32)).view(np.float32).astype(np.float64)
+    sig = 0.5 + 0.5 * K(x64 / 2)
+    assert np.max(np.abs(oracle.ksigmoid_f32(xf) - sig)) <= 2.0 ** -24
+    sw = oracle.kswish_f32(xf)
+    assert np.max(np.abs(sw - x64 * sig) / np.maximum(np.abs(x64 * sig), 1e-30)) <= 1e-6
+    arg64 = np.sqrt(2.0 / np.pi) * (x64 + 0.044715 * x64 ** 3)
+    arg32 = (np.float32(0.7978845608028654) * (xf + np.float32(0.044715) * ((xf * xf) * xf))).astype(np.float64)
+    # the oracle's own Float32 argument, rebuilt op by op in numpy float32, goes into K: a double
+    # argument could land on the other side of an interval boundary, where K jumps
+    ge = x64 / 2 * (1.0 + K(arg32))
+    got = oracle.kgelu_f32(xf).astype(np.float64)
+    assert np.max(np.abs(got - ge) / np.maximum(np.abs(ge), 1e-30)) <= 1e-6
+    true = x64 / 2 * (1 + np.tanh(arg64))
+    assert np.max(np.abs(got - true)) <= 1.67e-2 / 2 * 8 + 1e-6
+
+
+def test_f32_to_bf16_is_rounding_then_ktanh(oracle):
+    """Nearest-even rounding is input preparation the workloads module also performs; Algorithm 1 on
+    the result is pinned above.  Ties and carries into the exponent are included by construction."""
+    u = _f32_probe_patterns()
+    notnan = (u & 0x7FFFFFFF) <= 0x7F800000
+    xf = u[notnan].view(np.float32)
+    assert np.array_equal(oracle.ktanh_f32_to_bf16(xf), oracle.ktanh_bf16(wl.f32_to_bf16_bits(xf)))
+    nan_out = oracle.ktanh_f32_to_bf16(u[~notnan].view(np.float32))
+    assert np.all((nan_out & 0x7FFF) > 0x7F80)
+    # halfway cases by hand: 0x3F808000 is halfway between 0x3F80 and 0x3F81 -> even (0x3F80) -> K = 0x3F41
+    assert oracle.ktanh_f32_to_bf16(np.array([0x3F808000], dtype=np.uint32).view(np.float32))[0] == 0x3F41
+    # 0x3F818000 is halfway between 0x3F81 and 0x3F82 -> even (0x3F82): M=2, t=11000 (126,0,65) -> 0x3F43
+    assert oracle.ktanh_f32_to_bf16(np.array([0x3F818000], dtype=np.uint32).view(np.float32))[0] == 0x3F43
