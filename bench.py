@@ -195,7 +195,16 @@ def run_extras(torch, binding, wl, upload, xs, ys):
     y3 = [torch.empty_like(t) for t in x3]
     record("ktanh_f32", "2^28 fp32, uniform[-8,8) + 5% N(0,0.01^2), seed 190903, 2 rotating buffer pairs",
            lambda i: binding.ktanh_f32(x3[i % 2], out=y3[i % 2]), x3[0].numel(), 8, 100, 4)
-    del x3, y3
+    x3f = [t.view(torch.float32) for t in x3]
+    y3f = [t.view(torch.float32) for t in y3]
+    for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32"):
+        fn = getattr(binding, name)
+        record(name, "same 2^28 fp32 tensor, fp32 in and out, 2 rotating buffer pairs",
+               lambda i, fn=fn: fn(x3f[i % 2], out=y3f[i % 2]), x3[0].numel(), 8, 60, 4)
+    y3h = [torch.empty(x3[0].numel(), dtype=torch.bfloat16, device=x3[0].device) for _ in range(2)]
+    record("ktanh_f32_to_bf16", "same 2^28 fp32 tensor in, bf16 out (conversion fused into the load)",
+           lambda i: binding.ktanh_f32_to_bf16(x3f[i % 2], out=y3h[i % 2]), x3[0].numel(), 6, 60, 4)
+    del x3, y3, x3f, y3f, y3h
 
     gates_h, c0_h = wl.lstm_cell_inputs()
     gates, c0 = upload(gates_h), torch.from_numpy(c0_h).to("cuda:0")

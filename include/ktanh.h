@@ -129,6 +129,30 @@ ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n, const k
 ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n, const ktanh_lut64_t *lut,
                            ktanh_stream_t stream);
 
+/* ---- Float32 tensors -----------------------------------------------------------------------------
+ * The Section 1 identities on Float32 data with the Float32 form of Algorithm 1 (ktanh_f32) inside;
+ * nothing is rounded to BFloat16.  IEEE Float32, one rounding per operation, in this order:
+ *   ksigmoid_f32(x) = 0.5 * Kf(0.5 x) + 0.5
+ *   kswish_f32(x)   = x * (0.5 * Kf(0.5 x) + 0.5)
+ *   kgelu_f32(x)    = (0.5 x) * (1 + Kf(c * (x + a * ((x*x)*x))))
+ * in, out: device, n elements each, 4-byte aligned (16-byte congruent pointers take the vector path).
+ * NaN in gives NaN out. */
+ktanh_status_t ksigmoid_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                            ktanh_stream_t stream);
+ktanh_status_t kswish_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                          ktanh_stream_t stream);
+ktanh_status_t kgelu_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                         ktanh_stream_t stream);
+
+/* K-TanH on BFloat16 inputs that arrive as Float32: each value is rounded to BFloat16 (nearest even)
+ * and goes through ktanh_bf16 -- the conversion Section 2.5 leaves out of the paper's cycle count,
+ * fused into the load (6 bytes of traffic per element instead of 4 + 4 + 4).
+ * in: device, n Float32, 4-byte aligned; out: device, n BFloat16, 2-byte aligned.  The vector path
+ * needs `in` 16-byte and `out` 8-byte aligned after the same number of peeled elements; other
+ * alignments take an element-wise kernel.  NaN in gives NaN out (which NaN is unspecified). */
+ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
+                                 ktanh_stream_t stream);
+
 /* Element-wise part of an LSTM cell with K-TanH non-linearities (the recurrent GNMT workload of
  * Section 3 is what it serves; Sigmoid as in Section 1), over T consecutive time steps whose gate
  * pre-activations are all given:

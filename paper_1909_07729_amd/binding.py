@@ -18,7 +18,8 @@ INTERVALS = 32
 
 EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "ktanh_bf16",
            "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell",
-           "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32")
+           "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32",
+           "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16")
 
 
 class KtanhLut(ctypes.Structure):
@@ -91,6 +92,10 @@ def load_library() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         lib.klstm_cell.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp, vp]
         lib.klstm_cell.restype = ctypes.c_int
+        for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, sz, lp, vp]
+            fn.restype = ctypes.c_int
         lp64 = ctypes.POINTER(KtanhLut64)
         lib.ktanh_fit_lut.argtypes = [lp]
         lib.ktanh_fit_lut.restype = ctypes.c_int
@@ -210,6 +215,34 @@ def kswish(x, out=None, lut=None, stream=None):
 
 def kgelu(x, out=None, lut=None, stream=None):
     return _elementwise("kgelu", x, out, lut, stream, _BF16_VIEWS)
+
+
+def ksigmoid_f32(x, out=None, lut=None, stream=None):
+    """Sigmoid on a Float32 tensor through the Float32 K-TanH."""
+    return _elementwise("ksigmoid_f32", x, out, lut, stream, (torch.float32,))
+
+
+def kswish_f32(x, out=None, lut=None, stream=None):
+    return _elementwise("kswish_f32", x, out, lut, stream, (torch.float32,))
+
+
+def kgelu_f32(x, out=None, lut=None, stream=None):
+    return _elementwise("kgelu_f32", x, out, lut, stream, (torch.float32,))
+
+
+def ktanh_f32_to_bf16(x, out=None, lut=None, stream=None):
+    """Float32 tensor in, K-TanH of its BFloat16 rounding out (a bfloat16 tensor unless given)."""
+    _check(x, _F32_VIEWS, "in")
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
+    _check(out, _BF16_VIEWS, "out")
+    if out.numel() != x.numel():
+        raise ValueError("in and out differ in size")
+    st = load_library().ktanh_f32_to_bf16(x.data_ptr(), out.data_ptr(), x.numel(), _lut_arg(lut),
+                                          _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_f32_to_bf16")
+    return out
 
 
 def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None):

@@ -235,11 +235,34 @@ __device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
                  apply_pair<OP>(v.w, tab)};
 }
 
-template <bool WIDE>
+// One Float32 element of a Float32-tensor operation.
+//   Sigmoid: 0.5 * t is exact for every K output t that can change the sum, so multiply-add fuses.
+//   GELU: (x/2) * (1 + t) and x * (0.5 + 0.5 t) are the same real product and round alike.
+template <int OP>
+__device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &tab)
+{
+    if constexpr (OP == OP_TANH || OP == OP_TANH64) {
+        return ktanh_f32_one<OP == OP_TANH64>(u, tab);
+    } else if constexpr (OP == OP_SIGMOID || OP == OP_SWISH) {
+        const float x = __uint_as_float(u);
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * x), tab));
+        const float sg = __builtin_fmaf(0.5f, t, 0.5f);
+        return __float_as_uint(OP == OP_SIGMOID ? sg : x * sg);
+    } else {
+        const float a = 0.044715f;
+        const float c = 0.7978845608028654f;
+        const float x = __uint_as_float(u);
+        const float arg = c * (x + a * ((x * x) * x));
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(arg), tab));
+        return __float_as_uint(x * __builtin_fmaf(0.5f, t, 0.5f));
+    }
+}
+
+template <int OP>
 __device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
 {
-    return uint4{ktanh_f32_one<WIDE>(v.x, tab), ktanh_f32_one<WIDE>(v.y, tab),
-                 ktanh_f32_one<WIDE>(v.z, tab), ktanh_f32_one<WIDE>(v.w, tab)};
+    return uint4{apply_f32_one<OP>(v.x, tab), apply_f32_one<OP>(v.y, tab),
+                 apply_f32_one<OP>(v.z, tab), apply_f32_one<OP>(v.w, tab)};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -259,7 +282,7 @@ struct EdgeArgs {
 template <bool F32, int OP>
 __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
 {
-    if constexpr (F32) return apply_vec_f32<OP == OP_TANH64>(v, tab);
+    if constexpr (F32) return apply_vec_f32<OP>(v, tab);
     else return apply_vec_bf16<OP>(v, tab);
 }
 
@@ -297,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
-            x = ktanh_f32_one<OP == OP_TANH64>(x, tab);
+            x = apply_f32_one<OP>(x, tab);
             if (live) static_cast<uint32_t *>(edge.eout)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(edge.ein)[i];
@@ -322,13 +345,76 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(in)[i];
-            x = ktanh_f32_one<OP == OP_TANH64>(x, tab);
+            x = apply_f32_one<OP>(x, tab);
             if (live) static_cast<uint32_t *>(out)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(in)[i];
             x = apply_pair<OP>(x, tab);
             if (live) static_cast<uint16_t *>(out)[i] = (uint16_t)x;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Float32 in, BFloat16 out: round to nearest even (v_cvt_pk_bf16_f32), then K-TanH.  Each lane
+// reads two 128-bit vectors (4 Float32 each) and writes two 64-bit ones.
+__device__ __forceinline__ void store_stream(uint2 *p, uint2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+}
+
+__device__ __forceinline__ uint2 narrow_ktanh_vec(uint4 v, const LaneTable &tab)
+{
+    const uint32_t w0 = narrow_pair(__uint_as_float(v.x), __uint_as_float(v.y));
+    const uint32_t w1 = narrow_pair(__uint_as_float(v.z), __uint_as_float(v.w));
+    return uint2{ktanh_pair(w0, tab), ktanh_pair(w1, tab)};
+}
+
+__global__ __launch_bounds__(kBlock) void narrow_stream_kernel(const uint4 *__restrict__ vin,
+                                                               uint2 *__restrict__ vout,
+                                                               unsigned long long nvec,
+                                                               EdgeArgs edge, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * 2) + threadIdx.x;
+    uint4 v[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        v[u] = uint4{0u, 0u, 0u, 0u};
+        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
+    }
+    uint2 o[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) o[u] = narrow_ktanh_vec(v[u], tab);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, o[u]);
+
+    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+        const unsigned k = threadIdx.x;
+        const bool live = k < edge.n_edge;
+        const unsigned long long i = k < edge.n_head ? k : edge.n_total - edge.n_edge + k;
+        uint32_t x = 0;
+        if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
+        x = ktanh_pair(narrow_pair(__uint_as_float(x), 0.0f), tab);
+        if (live) static_cast<uint16_t *>(edge.eout)[i] = (uint16_t)x;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void narrow_element_kernel(const uint32_t *__restrict__ in,
+                                                                uint16_t *__restrict__ out,
+                                                                unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n;
+         base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool live = i < n;
+        uint32_t x = 0;
+        if (live) x = in[i];
+        x = ktanh_pair(narrow_pair(__uint_as_float(x), 0.0f), tab);
+        if (live) out[i] = (uint16_t)x;
     }
 }
 
@@ -572,6 +658,63 @@ extern "C" ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n,
                                 const ktanh_lut_t *lut, ktanh_stream_t stream)
 {
     return launch_elementwise<false, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                       ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                     ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                    ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n,
+                                            const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (n == 0) return KT_OK;
+    if (in == nullptr || out == nullptr) return KT_ERR_NULL;
+    const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
+    if (ain % 4 != 0 || aout % 2 != 0) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    if (st != KT_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    size_t head = ((16 - (ain & 15)) & 15) / 4;  // elements until `in` is 16-byte aligned
+    if (head > n) head = n;
+    if ((aout + 2 * head) % 8 == 0) {
+        const size_t nvec = (n - head) / 4;
+        const size_t tail = n - head - nvec * 4;
+        EdgeArgs edge;
+        edge.ein = in;
+        edge.eout = out;
+        edge.n_total = n;
+        edge.n_head = (unsigned)head;
+        edge.n_edge = (unsigned)(head + tail);
+        size_t tiles = (nvec + (size_t)kBlock * 2 - 1) / ((size_t)kBlock * 2);
+        if (tiles == 0) tiles = 1;
+        hipLaunchKernelGGL(narrow_stream_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, s,
+                           reinterpret_cast<const uint4 *>(in + head),
+                           reinterpret_cast<uint2 *>(out + head), (unsigned long long)nvec, edge, pack);
+    } else {
+        const size_t want = (n + kBlock - 1) / kBlock;
+        const size_t max_blocks = (size_t)compute_units() * kBlocksPerCu;
+        hipLaunchKernelGGL(narrow_element_kernel, dim3((unsigned)(want < max_blocks ? want : max_blocks)),
+                           dim3(kBlock), 0, s, reinterpret_cast<const uint32_t *>(in), out,
+                           (unsigned long long)n, pack);
+    }
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
 }
 
 extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out,

@@ -66,7 +66,8 @@ def test_argument_errors_are_returned_before_any_launch(binding):
     lib = binding.load_library()
     null = ctypes.c_void_p(0)
     fake = ctypes.c_void_p(0x1000)                # never dereferenced: rejected on the host
-    for name in ("ktanh_bf16", "ktanh_f32", "ksigmoid", "kswish", "kgelu"):
+    for name in ("ktanh_bf16", "ktanh_f32", "ksigmoid", "kswish", "kgelu", "ksigmoid_f32", "kswish_f32",
+                 "kgelu_f32", "ktanh_f32_to_bf16"):
         fn = getattr(lib, name)
         assert fn(null, null, 0, None, null) == 0             # n == 0: nothing to do
         assert fn(null, fake, 8, None, null) == 1

@@ -282,3 +282,76 @@ def test_ktanh64_full_size(gpu, oracle):
     u = wl.f32_mixture(1 << 26)
     got = _to_host(binding.ktanh64_f32(_to_dev(torch, u)), np.uint32)
     assert np.array_equal(got, oracle.ktanh64_f32(u))
+
+
+# ------------------------------------------------------------------ Float32 tensors
+def _assert_f32_equal(got, want, what):
+    gn, wn = np.isnan(got), np.isnan(want)
+    assert np.array_equal(gn, wn), f"{what}: NaN positions differ"
+    bad = np.nonzero((got.view(np.uint32) != want.view(np.uint32)) & ~wn)[0]
+    assert bad.size == 0, (f"{what}: {bad.size} mismatches, first at {bad[0]}: "
+                           f"got {got.view(np.uint32)[bad[0]]:08X} want {want.view(np.uint32)[bad[0]]:08X}")
+
+
+def _f32_cases():
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    rng = np.random.Generator(np.random.PCG64(14))
+    return np.concatenate([hi, hi | 0xFFFF, hi | 0x8000, hi | 0x7FFF, hi | 0x8001,
+                           rng.integers(0, 1 << 32, size=(1 << 21) + 7, dtype=np.uint64).astype(np.uint32),
+                           wl.f32_mixture((1 << 21) + 3, seed=15)])
+
+
+@pytest.mark.parametrize("name", ["ksigmoid_f32", "kswish_f32", "kgelu_f32"])
+def test_f32_derived_ops(gpu, oracle, name):
+    """Same Float32 operations in the same order on both sides: identical bits (the budget is 1e-6
+    relative), NaN by position."""
+    binding, torch = gpu
+    u = _f32_cases()
+    xf = u.view(np.float32)
+    with np.errstate(all="ignore"):
+        want = getattr(oracle, name)(xf)
+    got = getattr(binding, name)(torch.from_numpy(xf).to("cuda:0")).cpu().numpy()
+    _assert_f32_equal(got, want, name)
+    # ragged, unaligned, in place
+    n = 8192 * 3 + 5
+    xd = torch.from_numpy(xf[: n + 8].copy()).to("cuda:0")
+    for off_in, off_out in ((0, 0), (1, 1), (3, 2)):
+        outd = torch.full((n + 16,), 7.0, dtype=torch.float32, device="cuda:0")
+        getattr(binding, name)(xd[off_in:off_in + n], out=outd[4 + off_out:4 + off_out + n])
+        res = outd.cpu().numpy()
+        with np.errstate(all="ignore"):
+            _assert_f32_equal(res[4 + off_out:4 + off_out + n], getattr(oracle, name)(xf[off_in:off_in + n]), name)
+        assert np.all(res[:4 + off_out] == 7.0) and np.all(res[4 + off_out + n:] == 7.0)
+    getattr(binding, name)(xd, out=xd)
+    with np.errstate(all="ignore"):
+        _assert_f32_equal(xd.cpu().numpy(), getattr(oracle, name)(xf[: n + 8]), name + " in place")
+
+
+def test_f32_to_bf16(gpu, oracle):
+    binding, torch = gpu
+    u = _f32_cases()
+    xf = u.view(np.float32)
+    got = _to_host(binding.ktanh_f32_to_bf16(torch.from_numpy(xf).to("cuda:0")).view(torch.int16), np.uint16)
+    _assert_bf16_equal(got, oracle.ktanh_f32_to_bf16(xf), False, "ktanh_f32_to_bf16")
+    n = 8192 * 3 + 5
+    xd = torch.from_numpy(xf[: n + 8].copy()).to("cuda:0")
+    for off_in, off_out in ((0, 0), (1, 1), (3, 3), (0, 1), (2, 0), (1, 3), (0, 4)):
+        outd = torch.full((n + 24,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        binding.ktanh_f32_to_bf16(xd[off_in:off_in + n], out=outd[8 + off_out:8 + off_out + n])
+        res = _to_host(outd, np.uint16)
+        _assert_bf16_equal(res[8 + off_out:8 + off_out + n], oracle.ktanh_f32_to_bf16(xf[off_in:off_in + n]),
+                           False, f"offsets {off_in},{off_out}")
+        assert np.all(res[:8 + off_out] == 0x5A5A) and np.all(res[8 + off_out + n:] == 0x5A5A)
+    for n_small in (1, 3, 4, 5, 7, 8, 9, 511, 513):
+        got = _to_host(binding.ktanh_f32_to_bf16(xd[:n_small]).view(torch.int16), np.uint16)
+        _assert_bf16_equal(got, oracle.ktanh_f32_to_bf16(xf[:n_small]), False, f"n={n_small}")
+
+
+def test_f32_tensor_ops_full_size(gpu, oracle):
+    binding, torch = gpu
+    xf = wl.f32_mixture(1 << 26).view(np.float32)
+    xd = torch.from_numpy(xf).to("cuda:0")
+    for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32"):
+        _assert_f32_equal(getattr(binding, name)(xd).cpu().numpy(), getattr(oracle, name)(xf), name)
+    got = _to_host(binding.ktanh_f32_to_bf16(xd).view(torch.int16), np.uint16)
+    _assert_bf16_equal(got, oracle.ktanh_f32_to_bf16(xf), False, "ktanh_f32_to_bf16")
