@@ -3,6 +3,7 @@ declares, carries the paper's table, validates tables, and rejects bad arguments
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -127,3 +128,28 @@ def test_lut64_validation(binding):
         assert fn(null, fake, 8, None, null) == 1
         assert fn(ctypes.c_void_p(0x1001), fake, 8, None, null) == 2
         assert fn(fake, fake, 8, ctypes.byref(bad), null) == 3
+
+
+def test_header_is_valid_c_and_host_entry_points_work_from_c(binding, tmp_path):
+    """include/ktanh.h compiled as strict C99 by gcc, linked against the built library."""
+    exe = tmp_path / "abi_check"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "host_c", "abi_check.c"),
+                    "-o", str(exe), "-L", libdir, "-lktanh", f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    assert out.strip() == "KT_OK"
+
+
+def test_host_sources_under_address_and_ub_sanitizers(tmp_path):
+    """Table, validation, packing and fit are plain host C++: run them under ASan + UBSan."""
+    exe = tmp_path / "sanitize_host"
+    csrc = os.path.join(ROOT, "paper_1909_07729_amd", "csrc")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+                    "-I", os.path.join(ROOT, "include"), "-I", csrc,
+                    os.path.join(ROOT, "tests", "host_c", "sanitize_host.cpp"),
+                    os.path.join(csrc, "ktanh_lut.cpp"), os.path.join(csrc, "ktanh_fit.cpp"), "-o", str(exe)], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1")
+    res = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert "host sources clean" in res.stdout

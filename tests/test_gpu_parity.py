@@ -355,3 +355,62 @@ def test_f32_tensor_ops_full_size(gpu, oracle):
         _assert_f32_equal(getattr(binding, name)(xd).cpu().numpy(), getattr(oracle, name)(xf), name)
     got = _to_host(binding.ktanh_f32_to_bf16(xd).view(torch.int16), np.uint16)
     _assert_bf16_equal(got, oracle.ktanh_f32_to_bf16(xf), False, "ktanh_f32_to_bf16")
+
+
+# ------------------------------------------------------------------ sizes beyond 32-bit offsets
+def test_more_than_2_to_the_32_elements(gpu, oracle):
+    """8.6 GB tensors: element indices and byte offsets no longer fit 32 bits.  The input repeats the
+    65,536 BFloat16 patterns, so the expected output is the oracle's 65,536 answers repeated; the
+    comparison itself runs on the GPU (torch is only the ruler here)."""
+    binding, torch = gpu
+    base = wl.all_bf16_patterns()
+    n = (1 << 32) + 8 * 5 + 3
+    reps = n // base.size + 1
+    xd = _to_dev(torch, base).repeat(reps)[:n]
+    want = _to_dev(torch, oracle.ktanh_bf16(base)).repeat(reps)[:n]
+    got = binding.ktanh_bf16(xd)
+    assert got.numel() == n and torch.equal(got, want)
+    got = binding.ktanh_bf16(xd[1:])                     # peeled head, body beyond 4 GiB, ragged tail
+    assert torch.equal(got, want[1:])
+    del got, want
+    # Float32: the same patterns in the upper half of each word, 2^31 + 7 elements (8.6 GB)
+    n32 = (1 << 31) + 7
+    ud = (xd[:n32].to(torch.int32) << 16)
+    want32 = _to_dev(torch, oracle.ktanh_f32(base.astype(np.uint32) << 16)).repeat(n32 // base.size + 1)[:n32]
+    got32 = binding.ktanh_f32(ud)
+    assert torch.equal(got32, want32)
+
+
+def test_concurrent_host_threads_on_their_own_streams(gpu, oracle):
+    """The entry points keep no mutable state: four host threads, each with its own stream, tables
+    and tensors, interleave their calls freely."""
+    import threading
+    binding, torch = gpu
+    x = wl.mlp_preactivations(1 << 20, seed=91)
+    rows = oracle.table1().as_tuples()
+    results, errors = {}, []
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            my_rows = list(rows)
+            my_rows[24] = (126, 0, 60 + k)              # a different table per thread
+            klut, olut = binding.KtanhLut.from_tuples(my_rows), oracle.OracleLut.from_tuples(my_rows)
+            with torch.cuda.stream(stream):
+                xd = _to_dev(torch, x)
+                outs = [binding.kgelu(binding.ktanh_bf16(xd, lut=klut, stream=stream), lut=klut, stream=stream)
+                        for _ in range(20)]
+            stream.synchronize()
+            want = oracle.kgelu(oracle.ktanh_bf16(x, olut), olut)
+            results[k] = all(np.array_equal(_to_host(o, np.uint16), want) for o in outs)
+        except Exception as exc:                          # surfaced below, in the main thread
+            errors.append(repr(exc))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert results == {0: True, 1: True, 2: True, 3: True}
