@@ -1,0 +1,268 @@
+// Device-side building blocks of libktanh for gfx950: K-TanH (arXiv:1909.07729, Algorithm 1) on
+// packed BFloat16 pairs and on Float32, the derived activations, and the streaming accesses.
+//
+// The integer work of Algorithm 1 is done on two BFloat16 values per 32-bit register with packed
+// 16-bit instructions.  The parameter table is spread over the 64 lanes of each wavefront (one slot
+// per lane) and read with ds_bpermute_b32, which needs neither LDS storage nor a barrier.
+//
+// Because a cross-lane read returns 0 from a disabled lane, every table read executes with the
+// whole wavefront enabled: in the kernels, bounds only ever predicate the loads and stores around it.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "ktanh_pack.h"
+
+namespace ktanh_device {
+
+
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kBlock = 256;   // 4 wavefronts
+constexpr uint32_t kMag2 = 0x7FFF7FFFu;
+
+__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
+__device__ __forceinline__ i16x2 as_i16x2(uint32_t w) { return __builtin_bit_cast(i16x2, w); }
+__device__ __forceinline__ uint32_t as_u32(u16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ uint32_t as_u32(i16x2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ u16x2 splat(uint16_t v) { return u16x2{v, v}; }
+
+// 0xFFFF in each 16-bit half whose sign bit is set, 0 elsewhere: one packed arithmetic shift.
+// (Written as an instruction because the optimiser would otherwise turn "shift, then select on
+// the mask" into per-half compares and selects, which costs three times the issue slots.)
+__device__ __forceinline__ uint32_t sign_mask_pair(uint32_t d2)
+{
+    uint32_t m;
+    asm("v_pk_ashrrev_i16 %0, 15, %1 op_sel_hi:[0,1]" : "=v"(m) : "v"(d2));
+    return m;
+}
+
+// (a & mask) | (b & ~mask): one v_bfi_b32.
+__device__ __forceinline__ uint32_t bitsel(uint32_t mask, uint32_t a, uint32_t b)
+{
+    return (a & mask) | (b & ~mask);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The parameter table, one slot per lane (KtLutPack layout).  get() takes a byte address whose
+// bits [7:2] name the slot; higher bits are ignored by the instruction (lane = address / 4 mod 64).
+struct LaneTable {
+    uint32_t mine;
+    __device__ __forceinline__ explicit LaneTable(const KtLutPack &pack)
+        : mine(pack.slot[threadIdx.x & 63])
+    {
+    }
+    __device__ __forceinline__ uint32_t get(uint32_t slot_times_4) const
+    {
+        return (uint32_t)__builtin_amdgcn_ds_bpermute((int)slot_times_4, (int)mine);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Algorithm 1 on two BFloat16 magnitudes held in one register (sign bits clear, NaN not handled).
+//   slot      = low six bits of (E_i, M_i[6:4]) after clamping |x| to 4.0, so that everything
+//               beyond T2 reads the saturation slot and needs no test of its own;
+//   table out = (E_t << 7) + b_t + (M_i >> r_t).  Every slot belongs to one input exponent E_i, and
+//               (|x| >> r) = (E_i << (7 - r)) + (M_i >> r) exactly for r <= 7, so the slot stores
+//               base_t = (E_t << 7) + b_t - (E_i << (7 - r_t)) and the magnitude is shifted whole:
+//               no mantissa mask.  (The saturation slot shifts by 15, which leaves 0.)
+//   |x| < T1  = input passed through.
+__device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTable &tab)
+{
+    const uint32_t mc2 = as_u32(__builtin_elementwise_min(as_u16x2(mag2), splat(0x4080)));
+    const uint32_t e_lo = tab.get(mc2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
+    const uint32_t e_hi = tab.get(mc2 >> 18);  // same bits of the high value
+    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
+    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mc2) >> as_u16x2(r2)));
+    // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
+    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    return bitsel(pass, mag2, lut2);
+}
+
+// The same with a 64-interval table (index = 2 low exponent bits, 4 high mantissa bits): all 64
+// lanes hold table entries, so saturation is a select of its own.
+__device__ __forceinline__ uint32_t ktanh64_mag_pair(uint32_t mag2, const LaneTable &tab)
+{
+    const uint32_t e_lo = tab.get(mag2 >> 1);   // bits [7:2] <- bits [8:3] of the low value
+    const uint32_t e_hi = tab.get(mag2 >> 17);  // same bits of the high value
+    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
+    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mag2) >> as_u16x2(r2)));
+    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    const uint32_t beyond = sign_mask_pair(as_u32(as_i16x2(0x407F407Fu) - as_i16x2(mag2)));
+    return bitsel(beyond, 0x3F803F80u, bitsel(pass, mag2, lut2));
+}
+
+// 0xFFFF in each half that holds a NaN magnitude (> 0x7F80).
+__device__ __forceinline__ uint32_t nan_mask_pair(uint32_t mag2)
+{
+    return sign_mask_pair(as_u32(as_i16x2(0x7F807F80u) - as_i16x2(mag2)));
+}
+
+// K-TanH of two BFloat16 values, signs included.  NANS = false leaves out the NaN rule (a NaN then
+// comes out as +-1): for callers that have already established that no NaN can reach this point.
+template <bool NANS = true, bool WIDE = false>
+__device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
+{
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t res =
+        bitsel(kMag2, WIDE ? ktanh64_mag_pair(mag2, tab) : ktanh_mag_pair(mag2, tab), w);
+    if constexpr (!NANS) return res;
+    return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
+}
+
+// True in a lane where any of the given BFloat16 magnitude pairs holds a NaN.
+__device__ __forceinline__ bool any_nan_pair(uint32_t mag2)
+{
+    return as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x7F80))) != 0u;
+}
+__device__ __forceinline__ uint32_t max_pair(uint32_t a2, uint32_t b2)
+{
+    return as_u32(__builtin_elementwise_max(as_u16x2(a2), as_u16x2(b2)));
+}
+
+// Algorithm 1 on one Float32 pattern: same slot from the same leading bits; the 8-bit parameters
+// act on the 23-bit mantissa, b_t aligned to its top seven bits.
+template <bool WIDE = false>
+__device__ __forceinline__ uint32_t ktanh_f32_one(uint32_t u, const LaneTable &tab)
+{
+    const uint32_t mag = u & 0x7FFFFFFFu;
+    const uint32_t mc = mag < 0x40800000u ? mag : 0x40800000u;
+    // 32 intervals: bits [7:2] <- bits [25:20] (slot 8 = saturation); 64 intervals: <- bits [24:19]
+    const uint32_t e = tab.get(WIDE ? mag >> 17 : mc >> 18);
+    // Float32 slots (kt_pack_lut*_f32) keep the plain base (E_t << 7) + b_t in the high half.
+    uint32_t lut = (e & 0xFFFF0000u) + ((mc & 0x007FFFFFu) >> (e & 31u));
+    if constexpr (WIDE) lut = mag < 0x40800000u ? lut : 0x3F800000u;
+    uint32_t res = mag < 0x3E800000u ? mag : lut;
+    res = mag > 0x7F800000u ? (mag | 0x00400000u) : res;
+    return res | (u & 0x80000000u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// BFloat16 <-> Float32.
+__device__ __forceinline__ float widen_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float widen_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Two Float32 -> two BFloat16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
+{
+    const bf16x2 h = __builtin_convertvector(f32x2{lo, hi}, bf16x2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+// 0.5 * K(0.5 x) + 0.5 in Float32 for both halves of w.
+//   Halving a BFloat16 is "exponent field minus one" whenever that field is at least 2; below that
+//   |x| < 2^-125, K passes its argument through and the result is 0.5 whatever the argument, so a
+//   saturating subtract of 0x80 from the magnitude stands for the multiply and the rounding.
+//   0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse.
+template <bool NANS = true>
+__device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &tab, float &s_lo,
+                                                  float &s_hi)
+{
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t half_mag2 = as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x0080)));
+    uint32_t t2 = bitsel(kMag2, ktanh_mag_pair(half_mag2, tab), w);
+    if constexpr (NANS)
+        t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
+    s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
+    s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+}
+
+// 128-bit streaming accesses: every byte is touched once.  Measured on tensors that come from HBM:
+// loads with the non-temporal hint gain 1-3 % over plain loads (on a tensor its producer left in the
+// 256 MB last-level cache the hint costs about 4 %); stores gain about 5 % from the hint and another
+// 1-2 % from system-scope write-through (sc0 sc1), which the compiler has no builtin for.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 load_stream(const uint4 *p)
+{
+    const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return uint4{t.x, t.y, t.z, t.w};
+}
+__device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
+{
+    const u32x4 t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(t) : "memory");
+}
+// One dword at `base` (uniform) + `byte_offset` (per lane).
+__device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offset, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, %2 sc0 sc1 nt"
+                 :
+                 : "v"(byte_offset), "v"(v), "s"(base)
+                 : "memory");
+}
+
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_TANH64 = 4 };
+
+template <int OP>
+__device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
+{
+    if constexpr (OP == OP_TANH) {
+        return ktanh_pair(w, tab);
+    } else if constexpr (OP == OP_TANH64) {
+        return ktanh_pair<true, true>(w, tab);
+    } else if constexpr (OP == OP_SIGMOID) {
+        float s_lo, s_hi;
+        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        return narrow_pair(s_lo, s_hi);
+    } else if constexpr (OP == OP_SWISH) {
+        float s_lo, s_hi;
+        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        return narrow_pair(widen_lo(w) * s_lo, widen_hi(w) * s_hi);
+    } else {
+        // GELU, tanh form: (x/2) * (1 + K(c * (x + a * x^3))).  (x/2) * (1 + t) and
+        // x * (0.5 + 0.5 t) are the same real product and round alike (halving is exact).
+        const float a = 0.044715f;
+        const float c = 0.7978845608028654f;
+        const float x_lo = widen_lo(w), x_hi = widen_hi(w);
+        const float u_lo = c * (x_lo + a * ((x_lo * x_lo) * x_lo));
+        const float u_hi = c * (x_hi + a * ((x_hi * x_hi) * x_hi));
+        const uint32_t t2 = ktanh_pair(narrow_pair(u_lo, u_hi), tab);
+        const float y_lo = x_lo * __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
+        const float y_hi = x_hi * __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+        return narrow_pair(y_lo, y_hi);
+    }
+}
+
+template <int OP>
+__device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
+{
+    return uint4{apply_pair<OP>(v.x, tab), apply_pair<OP>(v.y, tab), apply_pair<OP>(v.z, tab),
+                 apply_pair<OP>(v.w, tab)};
+}
+
+// One Float32 element of a Float32-tensor operation.
+//   Sigmoid: 0.5 * t is exact for every K output t that can change the sum, so multiply-add fuses.
+//   GELU: (x/2) * (1 + t) and x * (0.5 + 0.5 t) are the same real product and round alike.
+template <int OP>
+__device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &tab)
+{
+    if constexpr (OP == OP_TANH || OP == OP_TANH64) {
+        return ktanh_f32_one<OP == OP_TANH64>(u, tab);
+    } else if constexpr (OP == OP_SIGMOID || OP == OP_SWISH) {
+        const float x = __uint_as_float(u);
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * x), tab));
+        const float sg = __builtin_fmaf(0.5f, t, 0.5f);
+        return __float_as_uint(OP == OP_SIGMOID ? sg : x * sg);
+    } else {
+        const float a = 0.044715f;
+        const float c = 0.7978845608028654f;
+        const float x = __uint_as_float(u);
+        const float arg = c * (x + a * ((x * x) * x));
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(arg), tab));
+        return __float_as_uint(x * __builtin_fmaf(0.5f, t, 0.5f));
+    }
+}
+
+template <int OP>
+__device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
+{
+    return uint4{apply_f32_one<OP>(v.x, tab), apply_f32_one<OP>(v.y, tab),
+                 apply_f32_one<OP>(v.z, tab), apply_f32_one<OP>(v.w, tab)};
+}
+
+}  // namespace ktanh_device

@@ -1,0 +1,163 @@
+// libktanh: the fused LSTM-cell element-wise kernel and its entry point.
+#include "ktanh_device.h"
+
+using namespace ktanh_device;
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// LSTM cell: each lane owns two neighbouring cells of one batch row (one packed BFloat16 pair per
+// gate) and carries their state through all T steps.  The work per cell is about fifty vector
+// instructions against ten bytes of traffic, so the kernel wants many wavefronts per SIMD to overlap
+// arithmetic with memory rather than wide accesses; a wavefront's loads still cover 256 contiguous
+// bytes each.  The steps of one lane are sequential, so the gate words of the next kStages steps are
+// already on their way while a step is computed (a ring of register stages): without that the loop
+// would pay one full memory latency per step.
+constexpr int kStages = 4;
+
+struct GateWords {
+    uint32_t i, f, g, o;
+};
+
+// Byte offsets of a lane's four gate words inside one time step's [B][4H] gate matrix: 32-bit, so
+// that each load is "uniform 64-bit base + 32-bit lane offset" and needs no address arithmetic.
+struct GateOffsets {
+    unsigned i, f, g, o;
+};
+
+__device__ __forceinline__ uint32_t load_word(const uint32_t *base, unsigned byte_offset)
+{
+    return *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(base) + byte_offset);
+}
+
+__device__ __forceinline__ GateWords load_gates(const uint32_t *step_base, GateOffsets &at,
+                                                bool live)
+{
+    // The empty statement re-defines the four 32-bit offsets right where they are used, so that
+    // each access is selected as "scalar base + 32-bit vector offset"; otherwise their 64-bit
+    // extensions are hoisted out of the loop and every access pays a 64-bit vector add.
+    asm volatile("" : "+v"(at.i), "+v"(at.f), "+v"(at.g), "+v"(at.o));
+    GateWords q{0u, 0u, 0u, 0u};
+    if (live) {
+        q.i = load_word(step_base, at.i);
+        q.f = load_word(step_base, at.f);
+        q.g = load_word(step_base, at.g);
+        q.o = load_word(step_base, at.o);
+    }
+    return q;
+}
+
+__device__ __forceinline__ bool not_finite(float x)
+{
+    return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u;
+}
+
+// One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
+// NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
+// is NaN and the incoming state is finite (the state then stays finite: |c'| <= |c| + 1).
+template <bool NANS>
+__device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
+                                              const LaneTable &tab)
+{
+    float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
+    ksigmoid_f32_pair<NANS>(q.i, tab, i_lo, i_hi);
+    ksigmoid_f32_pair<NANS>(q.f, tab, f_lo, f_hi);
+    ksigmoid_f32_pair<NANS>(q.o, tab, o_lo, o_hi);
+    const uint32_t g2 = ktanh_pair<NANS>(q.g, tab);
+    // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
+    const float keep_lo = f_lo * c_lo, keep_hi = f_hi * c_hi;
+    const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
+    c_lo = keep_lo + add_lo;
+    c_hi = keep_hi + add_hi;
+    const uint32_t tc2 = ktanh_pair<NANS>(narrow_pair(c_lo, c_hi), tab);
+    return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
+}
+
+__global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
+                                                           const float2 *__restrict__ c_in,
+                                                           float2 *__restrict__ c_out,
+                                                           uint32_t *__restrict__ h_out, unsigned T,
+                                                           unsigned n_pairs, unsigned H2,
+                                                           KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned p = blockIdx.x * kBlock + threadIdx.x;
+    const bool live = p < n_pairs;
+    const unsigned b = live ? p / H2 : 0;
+    const unsigned j = live ? p % H2 : 0;
+    const unsigned long long row_step = 4ull * n_pairs;  // gate words per time step
+    GateOffsets at;
+    at.i = (b * 4u * H2 + j) * 4u;  // < 16 * n_pairs <= 2^32 (checked by the caller)
+    at.f = at.i + 4u * H2;
+    at.g = at.f + 4u * H2;
+    at.o = at.g + 4u * H2;
+
+    const unsigned h_at = 4u * p;  // byte offset of this lane's output word inside one step of h
+
+    GateWords stage[kStages];
+#pragma unroll
+    for (int s = 0; s < kStages; ++s)
+        stage[s] = load_gates(gates + s * row_step, at, live && s < (int)T);
+
+    float2 c = float2{0.f, 0.f};
+    if (live) c = c_in[p];
+    bool suspect = not_finite(c.x) || not_finite(c.y);
+
+    for (unsigned t0 = 0; t0 < T; t0 += kStages) {
+#pragma unroll
+        for (int s = 0; s < kStages; ++s) {
+            const unsigned t = t0 + s;
+            if (t < T) {  // uniform over the grid: the table reads below keep every lane enabled
+                const GateWords q = stage[s];
+                stage[s] = load_gates(gates + (unsigned long long)(t + kStages) * row_step, at,
+                                      live && t + kStages < T);
+                // NaNs are rare: one test per step for the whole wavefront picks the full rules
+                // only when some lane needs them (a wavefront-uniform branch, so that the
+                // cross-lane table reads still run with every lane enabled).
+                const uint32_t worst = max_pair(max_pair(q.i & kMag2, q.f & kMag2),
+                                                max_pair(q.g & kMag2, q.o & kMag2));
+                uint32_t h;
+                if (__builtin_amdgcn_ballot_w64(suspect || any_nan_pair(worst)) != 0) {
+                    h = lstm_step<true>(q, c.x, c.y, tab);
+                    suspect = not_finite(c.x) || not_finite(c.y);
+                } else {
+                    h = lstm_step<false>(q, c.x, c.y, tab);
+                }
+                if (live) store_stream(h_out + (unsigned long long)t * n_pairs, h_at, h);
+            }
+        }
+    }
+    if (live) c_out[p] = c;
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out,
+                                     uint16_t *h_out, size_t T, size_t B, size_t H,
+                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (T == 0 || B == 0 || H == 0) return KT_OK;
+    if (gates == nullptr || c_in == nullptr || c_out == nullptr || h_out == nullptr)
+        return KT_ERR_NULL;
+    if (H % 8 != 0) return KT_ERR_SHAPE;
+    // sizes: T*B*4H elements must stay far below 2^63, T and H/8 must fit 32 bits
+    if (T > 0x7FFFFFFFull || H / 2 > 0xFFFFFFFFull || B > ((size_t)1 << 40) ||
+        (B * (H / 8)) > ((size_t)1 << 40) / T)
+        return KT_ERR_SHAPE;
+    const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_in) |
+                          reinterpret_cast<uintptr_t>(c_out) | reinterpret_cast<uintptr_t>(h_out);
+    if (mis & 15) return KT_ERR_ALIGN;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    if (st != KT_OK) return st;
+
+    const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
+    if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
+    const unsigned long long blocks = (n_pairs + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
+                       reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
+                       reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
+                       (unsigned)(H / 2), pack);
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}

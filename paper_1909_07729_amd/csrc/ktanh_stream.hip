@@ -1,0 +1,337 @@
+// libktanh: the element-wise streaming kernels (K-TanH on BFloat16 / Float32, 32 or 64 intervals,
+// Sigmoid / Swish / GELU on both formats, Float32 -> BFloat16 K-TanH) and their entry points.
+//
+// Shape of every kernel: a pure HBM stream.  Each lane moves 128 bits per access (8 BFloat16 or
+// 4 Float32), a wavefront covers 1 KiB per access, and every block handles one tile and exits.
+#include "ktanh_device.h"
+
+using namespace ktanh_device;
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// Element-wise streaming kernel over `nvec` 128-bit vectors plus up to `n_edge` loose elements.
+//   vin, vout : 16-byte aligned body (nvec vectors)
+//   ein, eout : the whole tensor as elements; edge element k (k < n_head) is element k, edge
+//               element k >= n_head is element n_total - n_edge + k (the ragged tail)
+// F32 selects the Float32 K-TanH (OP ignored), else the BFloat16 operation OP.
+struct EdgeArgs {
+    const void *ein;
+    void *eout;
+    unsigned long long n_total;
+    unsigned n_head;
+    unsigned n_edge;  // head + tail elements, < 64
+};
+
+template <bool F32, int OP>
+__device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
+{
+    if constexpr (F32) return apply_vec_f32<OP>(v, tab);
+    else return apply_vec_bf16<OP>(v, tab);
+}
+
+template <bool F32, int OP, int kUnroll>
+__global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict__ vin,
+                                                        uint4 *__restrict__ vout,
+                                                        unsigned long long nvec, EdgeArgs edge,
+                                                        KtLutPack pack)
+{
+    const LaneTable tab(pack);
+
+    // One tile of kBlock * kUnroll vectors per block, no loop: fresh blocks keep loads and stores
+    // of different tiles overlapped, which a grid-stride loop over the same tiles does not (measured:
+    // 6.5 against 6.0 TB/s on a 537 MB stream).  kUnroll = 1 moves the most bytes for the light
+    // operations; the Float32-heavy ones need two vectors per lane to hide their arithmetic.
+    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
+    uint4 v[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        v[u] = uint4{0u, 0u, 0u, 0u};
+        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP>(v[u], tab);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, v[u]);
+
+    // Loose elements before and after the aligned body: first wavefront of block 0.
+    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+        const unsigned k = threadIdx.x;
+        const bool live = k < edge.n_edge;
+        const unsigned long long i =
+            k < edge.n_head ? k : edge.n_total - edge.n_edge + k;
+        uint32_t x = 0;
+        if constexpr (F32) {
+            if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
+            x = apply_f32_one<OP>(x, tab);
+            if (live) static_cast<uint32_t *>(edge.eout)[i] = x;
+        } else {
+            if (live) x = static_cast<const uint16_t *>(edge.ein)[i];
+            x = apply_pair<OP>(x, tab);
+            if (live) static_cast<uint16_t *>(edge.eout)[i] = (uint16_t)x;
+        }
+    }
+}
+
+// Fallback when `in` and `out` disagree modulo 16 bytes: one element per lane and pass.
+template <bool F32, int OP>
+__global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict__ in,
+                                                         void *__restrict__ out,
+                                                         unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n;
+         base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool live = i < n;
+        uint32_t x = 0;
+        if constexpr (F32) {
+            if (live) x = static_cast<const uint32_t *>(in)[i];
+            x = apply_f32_one<OP>(x, tab);
+            if (live) static_cast<uint32_t *>(out)[i] = x;
+        } else {
+            if (live) x = static_cast<const uint16_t *>(in)[i];
+            x = apply_pair<OP>(x, tab);
+            if (live) static_cast<uint16_t *>(out)[i] = (uint16_t)x;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Float32 in, BFloat16 out: round to nearest even (v_cvt_pk_bf16_f32), then K-TanH.  Each lane
+// reads two 128-bit vectors (4 Float32 each) and writes two 64-bit ones.
+__device__ __forceinline__ void store_stream(uint2 *p, uint2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+}
+
+__device__ __forceinline__ uint2 narrow_ktanh_vec(uint4 v, const LaneTable &tab)
+{
+    const uint32_t w0 = narrow_pair(__uint_as_float(v.x), __uint_as_float(v.y));
+    const uint32_t w1 = narrow_pair(__uint_as_float(v.z), __uint_as_float(v.w));
+    return uint2{ktanh_pair(w0, tab), ktanh_pair(w1, tab)};
+}
+
+__global__ __launch_bounds__(kBlock) void narrow_stream_kernel(const uint4 *__restrict__ vin,
+                                                               uint2 *__restrict__ vout,
+                                                               unsigned long long nvec,
+                                                               EdgeArgs edge, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * 2) + threadIdx.x;
+    uint4 v[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        v[u] = uint4{0u, 0u, 0u, 0u};
+        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
+    }
+    uint2 o[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) o[u] = narrow_ktanh_vec(v[u], tab);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, o[u]);
+
+    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+        const unsigned k = threadIdx.x;
+        const bool live = k < edge.n_edge;
+        const unsigned long long i = k < edge.n_head ? k : edge.n_total - edge.n_edge + k;
+        uint32_t x = 0;
+        if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
+        x = ktanh_pair(narrow_pair(__uint_as_float(x), 0.0f), tab);
+        if (live) static_cast<uint16_t *>(edge.eout)[i] = (uint16_t)x;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void narrow_element_kernel(const uint32_t *__restrict__ in,
+                                                                uint16_t *__restrict__ out,
+                                                                unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n;
+         base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool live = i < n;
+        uint32_t x = 0;
+        if (live) x = in[i];
+        x = ktanh_pair(narrow_pair(__uint_as_float(x), 0.0f), tab);
+        if (live) out[i] = (uint16_t)x;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side.
+int compute_units()
+{
+    static int cached = 0;  // benign race: every thread computes the same value
+    if (cached == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        cached = cus;
+    }
+    return cached;
+}
+
+constexpr unsigned kBlocksPerCu = 8;  // resident blocks per compute unit the grid is sized for
+
+ktanh_status_t pack_for(const ktanh_lut_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut_f32(lut, pack) : kt_pack_lut_bf16(lut, pack);
+}
+ktanh_status_t pack_for(const ktanh_lut64_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
+}
+
+template <bool F32, int OP, class Lut>
+ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut *lut,
+                                  ktanh_stream_t stream)
+{
+    constexpr size_t kElem = F32 ? 4 : 2;
+    constexpr size_t kPerVec = 16 / kElem;
+    if (n == 0) return KT_OK;
+    if (in == nullptr || out == nullptr) return KT_ERR_NULL;
+    const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
+    if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
+    KtLutPack pack;
+    const ktanh_status_t st = pack_for(lut, F32, &pack);
+    if (st != KT_OK) return st;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned max_blocks = (unsigned)compute_units() * kBlocksPerCu;
+
+    if ((ain & 15) == (aout & 15)) {
+        size_t head = ((16 - (ain & 15)) & 15) / kElem;
+        if (head > n) head = n;
+        const size_t nvec = (n - head) / kPerVec;
+        const size_t tail = n - head - nvec * kPerVec;
+        EdgeArgs edge;
+        edge.ein = in;
+        edge.eout = out;
+        edge.n_total = n;
+        edge.n_head = (unsigned)head;
+        edge.n_edge = (unsigned)(head + tail);
+        const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
+        uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
+        constexpr int kUnroll = (F32 || OP == OP_TANH || OP == OP_TANH64) ? 1 : 2;
+        size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
+        if (tiles == 0) tiles = 1;  // edges only
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+        hipLaunchKernelGGL((stream_kernel<F32, OP, kUnroll>), dim3((unsigned)tiles), dim3(kBlock), 0,
+                           s, vin, vout, (unsigned long long)nvec, edge, pack);
+    } else {
+        const size_t want = (n + kBlock - 1) / kBlock;
+        const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
+        hipLaunchKernelGGL((element_kernel<F32, OP>), dim3(blocks), dim3(kBlock), 0, s, in, out,
+                           (unsigned long long)n, pack);
+    }
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t ktanh_bf16(const uint16_t *in, uint16_t *out, size_t n,
+                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TANH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh_f32(const uint32_t *in, uint32_t *out, size_t n,
+                                    const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_TANH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n,
+                                       const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TANH64>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n,
+                                      const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_TANH64>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid(const uint16_t *in, uint16_t *out, size_t n,
+                                   const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n,
+                                 const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n,
+                                const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                       ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                     ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
+                                    ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n,
+                                            const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (n == 0) return KT_OK;
+    if (in == nullptr || out == nullptr) return KT_ERR_NULL;
+    const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
+    if (ain % 4 != 0 || aout % 2 != 0) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    if (st != KT_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    size_t head = ((16 - (ain & 15)) & 15) / 4;  // elements until `in` is 16-byte aligned
+    if (head > n) head = n;
+    if ((aout + 2 * head) % 8 == 0) {
+        const size_t nvec = (n - head) / 4;
+        const size_t tail = n - head - nvec * 4;
+        EdgeArgs edge;
+        edge.ein = in;
+        edge.eout = out;
+        edge.n_total = n;
+        edge.n_head = (unsigned)head;
+        edge.n_edge = (unsigned)(head + tail);
+        size_t tiles = (nvec + (size_t)kBlock * 2 - 1) / ((size_t)kBlock * 2);
+        if (tiles == 0) tiles = 1;
+        hipLaunchKernelGGL(narrow_stream_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, s,
+                           reinterpret_cast<const uint4 *>(in + head),
+                           reinterpret_cast<uint2 *>(out + head), (unsigned long long)nvec, edge, pack);
+    } else {
+        const size_t want = (n + kBlock - 1) / kBlock;
+        const size_t max_blocks = (size_t)compute_units() * kBlocksPerCu;
+        hipLaunchKernelGGL(narrow_element_kernel, dim3((unsigned)(want < max_blocks ? want : max_blocks)),
+                           dim3(kBlock), 0, s, reinterpret_cast<const uint32_t *>(in), out,
+                           (unsigned long long)n, pack);
+    }
+    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}
