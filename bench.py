@@ -72,8 +72,8 @@ def time_steps(torch, launch, steps, warmup):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=5000)
+    ap.add_argument("--warmup", type=int, default=1000)   # the first ~10 ms after idle run slower
     ap.add_argument("--no-extra", action="store_true", help="headline only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--probe", action="store_true", help="few launches of each kernel + a copy, for rocprofv3")
@@ -171,13 +171,13 @@ def run_extras(torch, binding, wl, upload, xs, ys):
 
     # same tensor, same buffers every step: what a cache-resident activation sees
     record("ktanh_bf16_cache_resident", "[50,128,4096] bf16, one buffer pair reused (fits the 256 MB cache)",
-           lambda i: binding.ktanh_bf16(xs[0], out=ys[0]), xs[0].numel(), 4, 500)
+           lambda i: binding.ktanh_bf16(xs[0], out=ys[0]), xs[0].numel(), 4, 2000, 500)
 
     # yardstick: the runtime's own device-to-device copy of the same tensor (same bytes, no arithmetic)
     record("plain_copy_same_size", "hipMemcpyAsync device-to-device of the headline tensor, same 8 rotating pairs",
-           lambda i: ys[i % ROTATE].copy_(xs[i % ROTATE]), xs[0].numel(), 4, 1000, 20)
+           lambda i: ys[i % ROTATE].copy_(xs[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
     record("ktanh64_bf16", "[50,128,4096] bf16 as in the headline, 64-interval table, 8 rotating buffer pairs",
-           lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 1000, 20)
+           lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
 
     # the large tensors rotate as well: a 537 MB working set still keeps part of itself in the cache
     x4 = [upload(wl.mlp_preactivations())]
@@ -187,20 +187,20 @@ def run_extras(torch, binding, wl, upload, xs, ys):
     for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu"):
         fn = getattr(binding, name)
         record(f"{name}_mlp", "[8192,16384] bf16 ~ N(0,1), seed 190904, 4 rotating buffer pairs",
-               lambda i, fn=fn: fn(x4[i % 4], out=y4[i % 4]), x4[0].numel(), 4, 200, 8)
+               lambda i, fn=fn: fn(x4[i % 4], out=y4[i % 4]), x4[0].numel(), 4, 200, 100)
     del x4, y4
 
     x3 = [upload(wl.f32_mixture())]
     x3.append(x3[0].roll(4099))
     y3 = [torch.empty_like(t) for t in x3]
     record("ktanh_f32", "2^28 fp32, uniform[-8,8) + 5% N(0,0.01^2), seed 190903, 2 rotating buffer pairs",
-           lambda i: binding.ktanh_f32(x3[i % 2], out=y3[i % 2]), x3[0].numel(), 8, 100, 4)
+           lambda i: binding.ktanh_f32(x3[i % 2], out=y3[i % 2]), x3[0].numel(), 8, 100, 30)
     x3f = [t.view(torch.float32) for t in x3]
     y3f = [t.view(torch.float32) for t in y3]
     for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32"):
         fn = getattr(binding, name)
         record(name, "same 2^28 fp32 tensor, fp32 in and out, 2 rotating buffer pairs",
-               lambda i, fn=fn: fn(x3f[i % 2], out=y3f[i % 2]), x3[0].numel(), 8, 60, 4)
+               lambda i, fn=fn: fn(x3f[i % 2], out=y3f[i % 2]), x3[0].numel(), 8, 60, 10)
     y3h = [torch.empty(x3[0].numel(), dtype=torch.bfloat16, device=x3[0].device) for _ in range(2)]
     record("ktanh_f32_to_bf16", "same 2^28 fp32 tensor in, bf16 out (conversion fused into the load)",
            lambda i: binding.ktanh_f32_to_bf16(x3f[i % 2], out=y3h[i % 2]), x3[0].numel(), 6, 60, 4)
@@ -223,11 +223,11 @@ def run_extras(torch, binding, wl, upload, xs, ys):
             binding.klstm_cell(gates[t:t + 1], c, c_out=c, h_out=h[t:t + 1])
     record("klstm_cell_per_step", "gates [64,256,8192] bf16 ~ N(0,4), c [256,2048] fp32; 64 calls of one "
            "time step each (replayed as a HIP graph), figures per call",
-           lambda i: graph.replay(), cells * T, 18, 20, 3)
+           lambda i: graph.replay(), cells * T, 18, 40, 20)
     out["klstm_cell_per_step"]["avg_launch_us"] /= T
     record("klstm_cell_fused_T64", "same shapes, 3 rotating gate/h buffers; one call carries c through all 64 steps",
            lambda i: binding.klstm_cell(gates_rot[i % 3], c0, c_out=c, h_out=h_rot[i % 3]), cells * T,
-           10 + 8.0 / T, 60, 6)
+           10 + 8.0 / T, 90, 30)
     return out
 
 

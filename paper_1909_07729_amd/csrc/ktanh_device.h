@@ -20,7 +20,7 @@ typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kBlock = 256;   // 4 wavefronts
+constexpr int kBlock = 64;  // one wavefront per block: a finished wavefront's slot is refilled at once
 constexpr uint32_t kMag2 = 0x7FFF7FFFu;
 
 __device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }

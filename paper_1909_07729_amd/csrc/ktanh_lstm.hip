@@ -14,6 +14,7 @@ namespace {
 // already on their way while a step is computed (a ring of register stages): without that the loop
 // would pay one full memory latency per step.
 constexpr int kStages = 4;
+constexpr int kCellBlock = 256;  // four wavefronts per block measured best for the short per-step launch
 
 struct GateWords {
     uint32_t i, f, g, o;
@@ -73,7 +74,7 @@ __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, f
     return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
 }
 
-__global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
+__global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
                                                            const float2 *__restrict__ c_in,
                                                            float2 *__restrict__ c_out,
                                                            uint32_t *__restrict__ h_out, unsigned T,
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(kBlock) void lstm_cell_kernel(const uint32_t *__res
                                                            KtLutPack pack)
 {
     const LaneTable tab(pack);
-    const unsigned p = blockIdx.x * kBlock + threadIdx.x;
+    const unsigned p = blockIdx.x * kCellBlock + threadIdx.x;
     const bool live = p < n_pairs;
     const unsigned b = live ? p / H2 : 0;
     const unsigned j = live ? p % H2 : 0;
@@ -153,8 +154,8 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
 
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
     if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
-    const unsigned long long blocks = (n_pairs + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kBlock), 0,
+    const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
+    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kCellBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
                        reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
                        reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,

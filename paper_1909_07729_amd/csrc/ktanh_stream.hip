@@ -40,8 +40,9 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
 
     // One tile of kBlock * kUnroll vectors per block, no loop: fresh blocks keep loads and stores
     // of different tiles overlapped, which a grid-stride loop over the same tiles does not (measured:
-    // 6.5 against 6.0 TB/s on a 537 MB stream).  kUnroll = 1 moves the most bytes for the light
-    // operations; the Float32-heavy ones need two vectors per lane to hide their arithmetic.
+    // 6.5 against 6.0 TB/s on a 537 MB stream).  Single-wavefront blocks with one vector per lane
+    // measured best for every operation (5 % over 256-thread blocks on a 105 MB tensor): with 32
+    // independent wavefronts per compute unit even GELU's arithmetic hides under the stream.
     const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
     uint4 v[kUnroll];
 #pragma unroll
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
 
 // ---------------------------------------------------------------------------------------------
 // Float32 in, BFloat16 out: round to nearest even (v_cvt_pk_bf16_f32), then K-TanH.  Each lane
-// reads two 128-bit vectors (4 Float32 each) and writes two 64-bit ones.
+// reads one 128-bit vector (4 Float32) and writes one 64-bit one.
 __device__ __forceinline__ void store_stream(uint2 *p, uint2 v)
 {
     asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
@@ -120,19 +121,11 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(const uint4 *__re
                                                                EdgeArgs edge, KtLutPack pack)
 {
     const LaneTable tab(pack);
-    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * 2) + threadIdx.x;
-    uint4 v[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        v[u] = uint4{0u, 0u, 0u, 0u};
-        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
-    }
-    uint2 o[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) o[u] = narrow_ktanh_vec(v[u], tab);
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, o[u]);
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    uint4 v = uint4{0u, 0u, 0u, 0u};
+    if (at < nvec) v = load_stream(vin + at);
+    const uint2 o = narrow_ktanh_vec(v, tab);
+    if (at < nvec) store_stream(vout + at, o);
 
     if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
         const unsigned k = threadIdx.x;
@@ -178,7 +171,7 @@ int compute_units()
     return cached;
 }
 
-constexpr unsigned kBlocksPerCu = 8;  // resident blocks per compute unit the grid is sized for
+constexpr unsigned kBlocksPerCu = 32;  // resident blocks per compute unit the looping kernels' grid is sized for
 
 ktanh_status_t pack_for(const ktanh_lut_t *lut, bool f32, KtLutPack *pack)
 {
@@ -220,7 +213,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
         edge.n_edge = (unsigned)(head + tail);
         const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
         uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
-        constexpr int kUnroll = (F32 || OP == OP_TANH || OP == OP_TANH64) ? 1 : 2;
+        constexpr int kUnroll = 1;
         size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
@@ -321,8 +314,9 @@ extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size
         edge.n_total = n;
         edge.n_head = (unsigned)head;
         edge.n_edge = (unsigned)(head + tail);
-        size_t tiles = (nvec + (size_t)kBlock * 2 - 1) / ((size_t)kBlock * 2);
+        size_t tiles = (nvec + kBlock - 1) / kBlock;
         if (tiles == 0) tiles = 1;
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
         hipLaunchKernelGGL(narrow_stream_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, s,
                            reinterpret_cast<const uint4 *>(in + head),
                            reinterpret_cast<uint2 *>(out + head), (unsigned long long)nvec, edge, pack);
