@@ -272,8 +272,15 @@ def run_probe(torch, binding, wl, upload, headline, x):
     y3 = [torch.empty_like(t) for t in x3]
     for k in range(2):
         binding.ktanh_f32(x3[k], out=y3[k])
+    x3f, y3f = [t.view(torch.float32) for t in x3], [t.view(torch.float32) for t in y3]
+    for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32"):
+        for k in range(2):
+            getattr(binding, name)(x3f[k], out=y3f[k])
+    y3h = [torch.empty(x3[0].numel(), dtype=torch.bfloat16, device=x3[0].device) for _ in range(2)]
+    for k in range(2):
+        binding.ktanh_f32_to_bf16(x3f[k], out=y3h[k])
     torch.cuda.synchronize()
-    del x3, y3
+    del x3, y3, x3f, y3f, y3h
 
     gates_h, c0_h = wl.lstm_cell_inputs()
     gates, c0 = upload(gates_h), torch.from_numpy(c0_h).to("cuda:0")
