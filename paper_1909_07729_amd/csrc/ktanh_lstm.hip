@@ -55,7 +55,8 @@ __device__ __forceinline__ bool not_finite(float x)
 
 // One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
 // NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
-// is NaN and the incoming state is finite (the state then stays finite: |c'| <= |c| + 1).
+// is NaN, the incoming state is finite and the table keeps |K| <= 1 (the state then stays finite:
+// |c'| <= |c| + 1).
 template <bool NANS>
 __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
                                               const LaneTable &tab)
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
                                                            float2 *__restrict__ c_out,
                                                            uint32_t *__restrict__ h_out, unsigned T,
                                                            unsigned n_pairs, unsigned H2,
-                                                           KtLutPack pack)
+                                                           bool always_checked, KtLutPack pack)
 {
     const LaneTable tab(pack);
     const unsigned p = blockIdx.x * kCellBlock + threadIdx.x;
@@ -102,7 +103,8 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
 
     float2 c = float2{0.f, 0.f};
     if (live) c = c_in[p];
-    bool suspect = not_finite(c.x) || not_finite(c.y);
+    // always_checked: the caller's table lets |K| exceed 1, so the state may overflow on the way
+    bool suspect = always_checked || not_finite(c.x) || not_finite(c.y);
 
     for (unsigned t0 = 0; t0 < T; t0 += kStages) {
 #pragma unroll
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
                 uint32_t h;
                 if (__builtin_amdgcn_ballot_w64(suspect || any_nan_pair(worst)) != 0) {
                     h = lstm_step<true>(q, c.x, c.y, tab);
-                    suspect = not_finite(c.x) || not_finite(c.y);
+                    suspect = always_checked || not_finite(c.x) || not_finite(c.y);
                 } else {
                     h = lstm_step<false>(q, c.x, c.y, tab);
                 }
@@ -149,7 +151,8 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
                           reinterpret_cast<uintptr_t>(c_out) | reinterpret_cast<uintptr_t>(h_out);
     if (mis & 15) return KT_ERR_ALIGN;
     KtLutPack pack;
-    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    bool within_unit = true;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack, &within_unit);
     if (st != KT_OK) return st;
 
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
@@ -159,6 +162,6 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
                        reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
                        reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
-                       (unsigned)(H / 2), pack);
+                       (unsigned)(H / 2), !within_unit, pack);
     return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
 }

@@ -80,8 +80,17 @@ ktanh_status_t pack_slots(const ktanh_lut_t *lut, KtLutPack *pack, bool fold_inp
 
 }  // namespace
 
-ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack)
+ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack, bool *within_unit)
 {
+    if (within_unit != nullptr) {
+        const ktanh_lut_t *tab = lut != nullptr ? lut : &kTable1;
+        *within_unit = true;
+        for (int t = 0; t < KTANH_INTERVALS; ++t) {
+            const int last_m = ((t & 7) << 4) + 15;  // shift-and-add is monotone: the last input decides
+            const int largest = (tab->E[t] << 7) + (last_m >> (tab->r[t] & 7)) + tab->b[t];
+            if (largest > 0x3F80) *within_unit = false;
+        }
+    }
     return pack_slots(lut, pack, true);
 }
 

@@ -19,7 +19,9 @@ struct KtLutPack {
 };
 
 // Validate `lut` (NULL = Table 1) and fill `pack` for the BFloat16 kernels / the Float32 kernel.
-ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack);
+// `within_unit` (optional) is set to whether no table output can exceed 1.0 in magnitude, as is the
+// case for any table fitted to TanH; a caller's table may break it.
+ktanh_status_t kt_pack_lut_bf16(const ktanh_lut_t *lut, KtLutPack *pack, bool *within_unit = nullptr);
 ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack);
 
 // 64-interval tables: slot = t = (E_i & 3) << 4 | (M_i >> 3), all 64 slots are table entries (the

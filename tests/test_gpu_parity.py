@@ -414,3 +414,54 @@ def test_concurrent_host_threads_on_their_own_streams(gpu, oracle):
         t.join()
     assert not errors, errors
     assert results == {0: True, 1: True, 2: True, 3: True}
+
+
+# ------------------------------------------------------------------ arbitrary valid tables
+def _random_valid_table(rng, intervals):
+    """Any (E, r, b) the validator accepts: E in 1..254, r in 0..7, b such that (M >> r) + b stays in
+    0..127 over the interval -- including the extremes on purpose."""
+    per = 512 // intervals                           # 16 or 8 mantissas per interval
+    rows = []
+    for t in range(intervals):
+        j = t % (128 // per)
+        E = int(rng.choice([1, 2, 60, 124, 125, 126, 127, 128, 200, 254, int(rng.integers(1, 255))]))
+        r = int(rng.integers(0, 8))
+        lo, hi = -((j * per) >> r), 127 - ((j * per + per - 1) >> r)
+        b = int(rng.choice([lo, hi, int(rng.integers(lo, hi + 1))]))
+        rows.append((E, r, b))
+    return rows
+
+
+def test_random_valid_tables(gpu, oracle):
+    """The packed slots (folded input exponent, saturation slot, Float32 base) must reproduce
+    Algorithm 1 for every table the validator lets through, not just for Table 1."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(2024))
+    x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(20011, seed=5)])
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    u = np.concatenate([hi, hi | 0xFFFF, hi | rng.integers(0, 1 << 16, size=1 << 16, dtype=np.uint32)])
+    xd, ud = _to_dev(torch, x), _to_dev(torch, u)
+    gates, c0 = wl.lstm_cell_inputs(6, 3, 64)
+    gd, cd = _to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0")
+    for trial in range(12):
+        rows = _random_valid_table(rng, 32)
+        klut, olut = binding.KtanhLut.from_tuples(rows), oracle.OracleLut.from_tuples(rows)
+        assert binding.ktanh_lut_validate(klut) == 0, rows
+        for name in BF16_OPS:
+            got = _to_host(getattr(binding, name)(xd, lut=klut), np.uint16)
+            with np.errstate(all="ignore"):
+                want = getattr(oracle, name)(x, olut)
+            _assert_bf16_equal(got, want, name == "ktanh_bf16", f"{name} trial {trial}")
+        assert np.array_equal(_to_host(binding.ktanh_f32(ud, lut=klut), np.uint32), oracle.ktanh_f32(u, olut))
+        c_got, h_got = binding.klstm_cell(gd, cd, lut=klut)
+        with np.errstate(all="ignore"):
+            c_ref, h_ref = oracle.klstm_cell(gates, c0, olut)
+        cn = np.isnan(c_ref)
+        assert np.array_equal(np.isnan(c_got.cpu().numpy()), cn), f"lstm trial {trial}"
+        assert np.array_equal(c_got.cpu().numpy().view(np.uint32)[~cn], c_ref.view(np.uint32)[~cn])
+        _assert_bf16_equal(_to_host(h_got, np.uint16).ravel(), h_ref.ravel(), False, f"lstm h trial {trial}")
+        rows64 = _random_valid_table(rng, 64)
+        k64, o64 = binding.KtanhLut64.from_tuples(rows64), oracle.OracleLut64.from_tuples(rows64)
+        assert binding.ktanh_lut64_validate(k64) == 0, rows64
+        assert np.array_equal(_to_host(binding.ktanh64_bf16(xd, lut=k64), np.uint16), oracle.ktanh64_bf16(x, o64))
+        assert np.array_equal(_to_host(binding.ktanh64_f32(ud, lut=k64), np.uint32), oracle.ktanh64_f32(u, o64))
