@@ -293,12 +293,18 @@ static uint16_t narrow_rne(float f) /* Float32 -> BFloat16, round to nearest eve
 
 /* Sigmoid(x) = (1 + TanH(x/2)) / 2, TanH by K-TanH on the BFloat16 value of
  * x/2; the affine part stays in Float32. */
-static float ksigmoid_f32_of_bf16(uint16_t x, const oracle_lut *lut)
+static float ksigmoid_fields(uint16_t x, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                             const int8_t *Tb)
 {
     float half_x = 0.5f * widen(x);
-    float th = widen(ktanh_bf16_scalar(narrow_rne(half_x), lut));
+    float th = widen(ktanh_bf16_fields(narrow_rne(half_x), s, TE, Tr, Tb));
     float half_th = 0.5f * th;
     return half_th + 0.5f;
+}
+
+static float ksigmoid_f32_of_bf16(uint16_t x, const oracle_lut *lut)
+{
+    return ksigmoid_fields(x, 3, lut->E, lut->r, lut->b);
 }
 
 void oracle_ktanh_bf16(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut)
@@ -339,23 +345,27 @@ void oracle_kswish(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut
 }
 
 /* GELU(x) ~= x/2 * (1 + TanH(sqrt(2/pi) * (x + a x^3))), a = 0.044715. */
-void oracle_kgelu(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut)
+static uint16_t kgelu_fields(uint16_t xin, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                             const int8_t *Tb)
 {
     const float a = 0.044715f;
     const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
-    for (size_t i = 0; i < n; ++i) {
-        float x = widen(in[i]);
-        float x2 = x * x;
-        float x3 = x2 * x;
-        float ax3 = a * x3;
-        float inner = x + ax3;
-        float arg = c * inner;
-        float th = widen(ktanh_bf16_scalar(narrow_rne(arg), lut));
-        float half_x = 0.5f * x;
-        float one_plus = 1.0f + th;
-        float y = half_x * one_plus;
-        out[i] = narrow_rne(y);
-    }
+    float x = widen(xin);
+    float x2 = x * x;
+    float x3 = x2 * x;
+    float ax3 = a * x3;
+    float inner = x + ax3;
+    float arg = c * inner;
+    float th = widen(ktanh_bf16_fields(narrow_rne(arg), s, TE, Tr, Tb));
+    float half_x = 0.5f * x;
+    float one_plus = 1.0f + th;
+    float y = half_x * one_plus;
+    return narrow_rne(y);
+}
+
+void oracle_kgelu(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = kgelu_fields(in[i], 3, lut->E, lut->r, lut->b);
 }
 
 /* LSTM cell non-linearities over T time steps.
@@ -366,28 +376,63 @@ void oracle_kgelu(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut 
  *   h_out : [T][B][H] BFloat16 hidden output of every step
  * Per cell: i,f,o = Sigmoid, g = TanH, c' = f*c + i*g, h' = o * TanH(c'),
  * with TanH = K-TanH on BFloat16 inputs. */
-void oracle_klstm_cell(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
-                       size_t T, size_t B, size_t H, const oracle_lut *lut)
+static void klstm_fields(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                         size_t T, size_t B, size_t H, unsigned s, const uint8_t *TE,
+                         const uint8_t *Tr, const int8_t *Tb)
 {
     for (size_t bi = 0; bi < B; ++bi) {
         for (size_t j = 0; j < H; ++j) {
             float c = c_in[bi * H + j];
             for (size_t t = 0; t < T; ++t) {
                 const uint16_t *row = gates + (t * B + bi) * 4 * H;
-                float ig = ksigmoid_f32_of_bf16(row[0 * H + j], lut);
-                float fg = ksigmoid_f32_of_bf16(row[1 * H + j], lut);
-                float gg = widen(ktanh_bf16_scalar(row[2 * H + j], lut));
-                float og = ksigmoid_f32_of_bf16(row[3 * H + j], lut);
+                float ig = ksigmoid_fields(row[0 * H + j], s, TE, Tr, Tb);
+                float fg = ksigmoid_fields(row[1 * H + j], s, TE, Tr, Tb);
+                float gg = widen(ktanh_bf16_fields(row[2 * H + j], s, TE, Tr, Tb));
+                float og = ksigmoid_fields(row[3 * H + j], s, TE, Tr, Tb);
                 float keep = fg * c;
                 float add = ig * gg;
                 c = keep + add;
-                float tc = widen(ktanh_bf16_scalar(narrow_rne(c), lut));
+                float tc = widen(ktanh_bf16_fields(narrow_rne(c), s, TE, Tr, Tb));
                 float h = og * tc;
                 h_out[(t * B + bi) * H + j] = narrow_rne(h);
             }
             c_out[bi * H + j] = c;
         }
     }
+}
+
+void oracle_klstm_cell(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                       size_t T, size_t B, size_t H, const oracle_lut *lut)
+{
+    klstm_fields(gates, c_in, c_out, h_out, T, B, H, 3, lut->E, lut->r, lut->b);
+}
+
+/* The derived operations and the LSTM cell on 64-interval tables: same code, 4 index bits. */
+void oracle_ksigmoid64(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = narrow_rne(ksigmoid_fields(in[i], 4, lut->E, lut->r, lut->b));
+}
+
+void oracle_kswish64(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float x = widen(in[i]);
+        float sg = ksigmoid_fields(in[i], 4, lut->E, lut->r, lut->b);
+        float y = x * sg;
+        out[i] = narrow_rne(y);
+    }
+}
+
+void oracle_kgelu64(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = kgelu_fields(in[i], 4, lut->E, lut->r, lut->b);
+}
+
+void oracle_klstm_cell64(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                         size_t T, size_t B, size_t H, const oracle_lut64 *lut)
+{
+    klstm_fields(gates, c_in, c_out, h_out, T, B, H, 4, lut->E, lut->r, lut->b);
 }
 
 /* ------------------------------------------------------------------ */

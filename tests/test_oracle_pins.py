@@ -479,3 +479,29 @@ def test_f32_to_bf16_is_rounding_then_ktanh(oracle):
     assert oracle.ktanh_f32_to_bf16(np.array([0x3F808000], dtype=np.uint32).view(np.float32))[0] == 0x3F41
     # 0x3F818000 is halfway between 0x3F81 and 0x3F82 -> even (0x3F82): M=2, t=11000 (126,0,65) -> 0x3F43
     assert oracle.ktanh_f32_to_bf16(np.array([0x3F818000], dtype=np.uint32).view(np.float32))[0] == 0x3F43
+
+
+def test_derived_ops_on_64_interval_tables(oracle):
+    """Same identities around the 64-interval K-TanH (pinned above): float64 re-evaluation to 1 ulp,
+    one hand-worked value, and a table that repeats Table 1's entries must give the 32-interval
+    results bit for bit (the 64-entry code path with the 32-entry function)."""
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    K64 = lambda bits: _bf16_val(oracle.ktanh64_bf16(bits))
+    sig = (1.0 + K64(_round_f64_to_bf16(xv / 2))) / 2.0
+    assert np.max(_ulp_distance_bf16(oracle.ksigmoid64(x), _round_f64_to_bf16(sig))) <= 1
+    ok = np.abs(xv * sig) < 3.0e38
+    assert np.max(_ulp_distance_bf16(oracle.kswish64(x)[ok], _round_f64_to_bf16((xv * sig)[ok]))) <= 1
+    # x = 1: K64(0.5): E=126 M=0 -> t = 100000 -> fitted (125, 0, 111): 0x3E80 + 111 = 0x3EEF = 0.466796875
+    # (1 + 0.466796875) / 2 = 0.7333984375 -> BFloat16 0x3F3C (mantissa 59.75 -> 60)
+    assert oracle.fit_lut64().as_tuples()[32] == (125, 0, 111)
+    assert oracle.ksigmoid64(np.array([0x3F80], dtype=np.uint16))[0] == 0x3F3C
+    doubled = oracle.OracleLut64.from_tuples([oracle.table1().as_tuples()[((t >> 4) << 3) | ((t & 15) >> 1)] for t in range(64)])
+    xa = wl.all_bf16_patterns()
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu"):
+        wide_name = {"ktanh_bf16": "ktanh64_bf16"}.get(name, name + "64")
+        assert np.array_equal(getattr(oracle, wide_name)(xa, doubled), getattr(oracle, name)(xa)), name
+    gates, c0 = wl.lstm_cell_inputs(4, 3, 16)
+    c_a, h_a = oracle.klstm_cell64(gates, c0, doubled)
+    c_b, h_b = oracle.klstm_cell(gates, c0)
+    assert np.array_equal(c_a, c_b) and np.array_equal(h_a, h_b)
