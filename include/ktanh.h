@@ -129,6 +129,19 @@ ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n, const k
 ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n, const ktanh_lut64_t *lut,
                            ktanh_stream_t stream);
 
+/* ksigmoid, kswish, kgelu and klstm_cell (declared below and above) with a 64-interval table: same
+ * contracts, same operation sequences, K = ktanh64_bf16.  (The Float32-tensor activations exist for
+ * 32-interval tables only.) */
+ktanh_status_t ksigmoid64(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
+                          ktanh_stream_t stream);
+ktanh_status_t kswish64(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
+                        ktanh_stream_t stream);
+ktanh_status_t kgelu64(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
+                       ktanh_stream_t stream);
+ktanh_status_t klstm_cell64(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                            size_t T, size_t B, size_t H, const ktanh_lut64_t *lut,
+                            ktanh_stream_t stream);
+
 /* ---- Float32 tensors -----------------------------------------------------------------------------
  * The Section 1 identities on Float32 data with the Float32 form of Algorithm 1 (ktanh_f32) inside;
  * nothing is rounded to BFloat16.  IEEE Float32, one rounding per operation, in this order:

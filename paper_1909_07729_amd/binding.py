@@ -19,7 +19,8 @@ INTERVALS = 32
 EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "ktanh_bf16",
            "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell",
            "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32",
-           "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16")
+           "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
+           "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64")
 
 
 class KtanhLut(ctypes.Structure):
@@ -103,10 +104,12 @@ def load_library() -> ctypes.CDLL:
         lib.ktanh_fit_lut64.restype = ctypes.c_int
         lib.ktanh_lut64_validate.argtypes = [lp64]
         lib.ktanh_lut64_validate.restype = ctypes.c_int
-        for name in ("ktanh64_bf16", "ktanh64_f32"):
+        for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, sz, lp64, vp]
             fn.restype = ctypes.c_int
+        lib.klstm_cell64.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp64, vp]
+        lib.klstm_cell64.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -205,6 +208,18 @@ def ktanh64_f32(x, out=None, lut=None, stream=None):
     return _elementwise("ktanh64_f32", x, out, lut, stream, _F32_VIEWS)
 
 
+def ksigmoid64(x, out=None, lut=None, stream=None):
+    return _elementwise("ksigmoid64", x, out, lut, stream, _BF16_VIEWS)
+
+
+def kswish64(x, out=None, lut=None, stream=None):
+    return _elementwise("kswish64", x, out, lut, stream, _BF16_VIEWS)
+
+
+def kgelu64(x, out=None, lut=None, stream=None):
+    return _elementwise("kgelu64", x, out, lut, stream, _BF16_VIEWS)
+
+
 def ksigmoid(x, out=None, lut=None, stream=None):
     return _elementwise("ksigmoid", x, out, lut, stream, _BF16_VIEWS)
 
@@ -245,7 +260,12 @@ def ktanh_f32_to_bf16(x, out=None, lut=None, stream=None):
     return out
 
 
-def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None):
+def klstm_cell64(gates, c_in, c_out=None, h_out=None, lut=None, stream=None):
+    """``klstm_cell`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return klstm_cell(gates, c_in, c_out, h_out, lut, stream, _entry="klstm_cell64")
+
+
+def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None, _entry="klstm_cell"):
     """LSTM-cell element-wise step(s).  gates [T, B, 4H] BFloat16 (i|f|g|o), c_in [B, H] Float32.
 
     Returns (c_out [B, H] Float32, h_out [T, B, H] in the dtype of ``gates``).
@@ -266,8 +286,9 @@ def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None):
     _check(h_out, _BF16_VIEWS, "h_out")
     if tuple(c_out.shape) != (B, H) or tuple(h_out.shape) != (T, B, H):
         raise ValueError("c_out must be [B, H] and h_out [T, B, H]")
-    st = load_library().klstm_cell(gates.data_ptr(), c_in.data_ptr(), c_out.data_ptr(),
-                                   h_out.data_ptr(), T, B, H, _lut_arg(lut), _stream_handle(stream))
+    st = getattr(load_library(), _entry)(gates.data_ptr(), c_in.data_ptr(), c_out.data_ptr(),
+                                         h_out.data_ptr(), T, B, H, _lut_arg(lut),
+                                         _stream_handle(stream))
     if st != 0:
-        raise KtanhError(st, "klstm_cell")
+        raise KtanhError(st, _entry)
     return c_out, h_out

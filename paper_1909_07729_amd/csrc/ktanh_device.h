@@ -158,13 +158,14 @@ __device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
 //   |x| < 2^-125, K passes its argument through and the result is 0.5 whatever the argument, so a
 //   saturating subtract of 0x80 from the magnitude stands for the multiply and the rounding.
 //   0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse.
-template <bool NANS = true>
+template <bool NANS = true, bool WIDE = false>
 __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &tab, float &s_lo,
                                                   float &s_hi)
 {
     const uint32_t mag2 = w & kMag2;
     const uint32_t half_mag2 = as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x0080)));
-    uint32_t t2 = bitsel(kMag2, ktanh_mag_pair(half_mag2, tab), w);
+    uint32_t t2 = bitsel(
+        kMag2, WIDE ? ktanh64_mag_pair(half_mag2, tab) : ktanh_mag_pair(half_mag2, tab), w);
     if constexpr (NANS)
         t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
     s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
@@ -196,22 +197,21 @@ __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offse
                  : "memory");
 }
 
-enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_TANH64 = 4 };
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
 
-template <int OP>
+// WIDE selects the 64-interval table layout.
+template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
 {
     if constexpr (OP == OP_TANH) {
-        return ktanh_pair(w, tab);
-    } else if constexpr (OP == OP_TANH64) {
-        return ktanh_pair<true, true>(w, tab);
+        return ktanh_pair<true, WIDE>(w, tab);
     } else if constexpr (OP == OP_SIGMOID) {
         float s_lo, s_hi;
-        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        ksigmoid_f32_pair<true, WIDE>(w, tab, s_lo, s_hi);
         return narrow_pair(s_lo, s_hi);
     } else if constexpr (OP == OP_SWISH) {
         float s_lo, s_hi;
-        ksigmoid_f32_pair(w, tab, s_lo, s_hi);
+        ksigmoid_f32_pair<true, WIDE>(w, tab, s_lo, s_hi);
         return narrow_pair(widen_lo(w) * s_lo, widen_hi(w) * s_hi);
     } else {
         // GELU, tanh form: (x/2) * (1 + K(c * (x + a * x^3))).  (x/2) * (1 + t) and
@@ -221,28 +221,29 @@ __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
         const float x_lo = widen_lo(w), x_hi = widen_hi(w);
         const float u_lo = c * (x_lo + a * ((x_lo * x_lo) * x_lo));
         const float u_hi = c * (x_hi + a * ((x_hi * x_hi) * x_hi));
-        const uint32_t t2 = ktanh_pair(narrow_pair(u_lo, u_hi), tab);
+        const uint32_t t2 = ktanh_pair<true, WIDE>(narrow_pair(u_lo, u_hi), tab);
         const float y_lo = x_lo * __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
         const float y_hi = x_hi * __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
         return narrow_pair(y_lo, y_hi);
     }
 }
 
-template <int OP>
+template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
 {
-    return uint4{apply_pair<OP>(v.x, tab), apply_pair<OP>(v.y, tab), apply_pair<OP>(v.z, tab),
-                 apply_pair<OP>(v.w, tab)};
+    return uint4{apply_pair<OP, WIDE>(v.x, tab), apply_pair<OP, WIDE>(v.y, tab),
+                 apply_pair<OP, WIDE>(v.z, tab), apply_pair<OP, WIDE>(v.w, tab)};
 }
 
 // One Float32 element of a Float32-tensor operation.
 //   Sigmoid: 0.5 * t is exact for every K output t that can change the sum, so multiply-add fuses.
 //   GELU: (x/2) * (1 + t) and x * (0.5 + 0.5 t) are the same real product and round alike.
-template <int OP>
+template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &tab)
 {
-    if constexpr (OP == OP_TANH || OP == OP_TANH64) {
-        return ktanh_f32_one<OP == OP_TANH64>(u, tab);
+    static_assert(!WIDE || OP == OP_TANH, "Float32-tensor activations exist for 32 intervals only");
+    if constexpr (OP == OP_TANH) {
+        return ktanh_f32_one<WIDE>(u, tab);
     } else if constexpr (OP == OP_SIGMOID || OP == OP_SWISH) {
         const float x = __uint_as_float(u);
         const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * x), tab));
@@ -258,11 +259,11 @@ __device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &t
     }
 }
 
-template <int OP>
+template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
 {
-    return uint4{apply_f32_one<OP>(v.x, tab), apply_f32_one<OP>(v.y, tab),
-                 apply_f32_one<OP>(v.z, tab), apply_f32_one<OP>(v.w, tab)};
+    return uint4{apply_f32_one<OP, WIDE>(v.x, tab), apply_f32_one<OP, WIDE>(v.y, tab),
+                 apply_f32_one<OP, WIDE>(v.z, tab), apply_f32_one<OP, WIDE>(v.w, tab)};
 }
 
 }  // namespace ktanh_device

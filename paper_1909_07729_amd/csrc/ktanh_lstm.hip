@@ -57,24 +57,25 @@ __device__ __forceinline__ bool not_finite(float x)
 // NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
 // is NaN, the incoming state is finite and the table keeps |K| <= 1 (the state then stays finite:
 // |c'| <= |c| + 1).
-template <bool NANS>
+template <bool NANS, bool WIDE>
 __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
                                               const LaneTable &tab)
 {
     float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
-    ksigmoid_f32_pair<NANS>(q.i, tab, i_lo, i_hi);
-    ksigmoid_f32_pair<NANS>(q.f, tab, f_lo, f_hi);
-    ksigmoid_f32_pair<NANS>(q.o, tab, o_lo, o_hi);
-    const uint32_t g2 = ktanh_pair<NANS>(q.g, tab);
+    ksigmoid_f32_pair<NANS, WIDE>(q.i, tab, i_lo, i_hi);
+    ksigmoid_f32_pair<NANS, WIDE>(q.f, tab, f_lo, f_hi);
+    ksigmoid_f32_pair<NANS, WIDE>(q.o, tab, o_lo, o_hi);
+    const uint32_t g2 = ktanh_pair<NANS, WIDE>(q.g, tab);
     // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
     const float keep_lo = f_lo * c_lo, keep_hi = f_hi * c_hi;
     const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
     c_lo = keep_lo + add_lo;
     c_hi = keep_hi + add_hi;
-    const uint32_t tc2 = ktanh_pair<NANS>(narrow_pair(c_lo, c_hi), tab);
+    const uint32_t tc2 = ktanh_pair<NANS, WIDE>(narrow_pair(c_lo, c_hi), tab);
     return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
 }
 
+template <bool WIDE>
 __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
                                                            const float2 *__restrict__ c_in,
                                                            float2 *__restrict__ c_out,
@@ -121,10 +122,10 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
                                                 max_pair(q.g & kMag2, q.o & kMag2));
                 uint32_t h;
                 if (__builtin_amdgcn_ballot_w64(suspect || any_nan_pair(worst)) != 0) {
-                    h = lstm_step<true>(q, c.x, c.y, tab);
+                    h = lstm_step<true, WIDE>(q, c.x, c.y, tab);
                     suspect = always_checked || not_finite(c.x) || not_finite(c.y);
                 } else {
-                    h = lstm_step<false>(q, c.x, c.y, tab);
+                    h = lstm_step<false, WIDE>(q, c.x, c.y, tab);
                 }
                 if (live) store_stream(h_out + (unsigned long long)t * n_pairs, h_at, h);
             }
@@ -133,11 +134,18 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
     if (live) c_out[p] = c;
 }
 
-}  // namespace
+ktanh_status_t pack_cell(const ktanh_lut_t *lut, KtLutPack *pack, bool *within_unit)
+{
+    return kt_pack_lut_bf16(lut, pack, within_unit);
+}
+ktanh_status_t pack_cell(const ktanh_lut64_t *lut, KtLutPack *pack, bool *within_unit)
+{
+    return kt_pack_lut64_bf16(lut, pack, within_unit);
+}
 
-extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out,
-                                     uint16_t *h_out, size_t T, size_t B, size_t H,
-                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+template <bool WIDE, class Lut>
+ktanh_status_t launch_cell(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
+                           size_t T, size_t B, size_t H, const Lut *lut, ktanh_stream_t stream)
 {
     if (T == 0 || B == 0 || H == 0) return KT_OK;
     if (gates == nullptr || c_in == nullptr || c_out == nullptr || h_out == nullptr)
@@ -152,16 +160,32 @@ extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, f
     if (mis & 15) return KT_ERR_ALIGN;
     KtLutPack pack;
     bool within_unit = true;
-    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack, &within_unit);
+    const ktanh_status_t st = pack_cell(lut, &pack, &within_unit);
     if (st != KT_OK) return st;
 
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
     if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
     const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
-    hipLaunchKernelGGL(lstm_cell_kernel, dim3((unsigned)blocks), dim3(kCellBlock), 0,
+    hipLaunchKernelGGL(lstm_cell_kernel<WIDE>, dim3((unsigned)blocks), dim3(kCellBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
                        reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
                        reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
                        (unsigned)(H / 2), !within_unit, pack);
     return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out,
+                                     uint16_t *h_out, size_t T, size_t B, size_t H,
+                                     const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_cell<false>(gates, c_in, c_out, h_out, T, B, H, lut, stream);
+}
+
+extern "C" ktanh_status_t klstm_cell64(const uint16_t *gates, const float *c_in, float *c_out,
+                                       uint16_t *h_out, size_t T, size_t B, size_t H,
+                                       const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_cell<true>(gates, c_in, c_out, h_out, T, B, H, lut, stream);
 }

@@ -142,8 +142,17 @@ ktanh_status_t pack_slots64(const ktanh_lut64_t *lut, KtLutPack *pack, bool fold
 
 }  // namespace
 
-ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack)
+ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack, bool *within_unit)
 {
+    if (within_unit != nullptr) {
+        const ktanh_lut64_t *tab = lut != nullptr ? lut : fitted_lut64();
+        *within_unit = true;
+        for (int t = 0; t < KTANH_INTERVALS64; ++t) {
+            const int last_m = ((t & 15) << 3) + 7;
+            const int largest = (tab->E[t] << 7) + (last_m >> (tab->r[t] & 7)) + tab->b[t];
+            if (largest > 0x3F80) *within_unit = false;
+        }
+    }
     return pack_slots64(lut, pack, true);
 }
 

@@ -27,5 +27,6 @@ ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack);
 // 64-interval tables: slot = t = (E_i & 3) << 4 | (M_i >> 3), all 64 slots are table entries (the
 // saturation value has no slot of its own; the kernels select it).  Same slot format as above.
 // NULL = the fitted 64-interval table.
-ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack);
+ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack,
+                                  bool *within_unit = nullptr);
 ktanh_status_t kt_pack_lut64_f32(const ktanh_lut64_t *lut, KtLutPack *pack);

@@ -23,14 +23,14 @@ struct EdgeArgs {
     unsigned n_edge;  // head + tail elements, < 64
 };
 
-template <bool F32, int OP>
+template <bool F32, int OP, bool WIDE>
 __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
 {
-    if constexpr (F32) return apply_vec_f32<OP>(v, tab);
-    else return apply_vec_bf16<OP>(v, tab);
+    if constexpr (F32) return apply_vec_f32<OP, WIDE>(v, tab);
+    else return apply_vec_bf16<OP, WIDE>(v, tab);
 }
 
-template <bool F32, int OP, int kUnroll>
+template <bool F32, int OP, bool WIDE, int kUnroll>
 __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict__ vin,
                                                         uint4 *__restrict__ vout,
                                                         unsigned long long nvec, EdgeArgs edge,
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
         if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP>(v[u], tab);
+    for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP, WIDE>(v[u], tab);
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u)
         if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, v[u]);
@@ -65,18 +65,18 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(edge.ein)[i];
-            x = apply_f32_one<OP>(x, tab);
+            x = apply_f32_one<OP, WIDE>(x, tab);
             if (live) static_cast<uint32_t *>(edge.eout)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(edge.ein)[i];
-            x = apply_pair<OP>(x, tab);
+            x = apply_pair<OP, WIDE>(x, tab);
             if (live) static_cast<uint16_t *>(edge.eout)[i] = (uint16_t)x;
         }
     }
 }
 
 // Fallback when `in` and `out` disagree modulo 16 bytes: one element per lane and pass.
-template <bool F32, int OP>
+template <bool F32, int OP, bool WIDE>
 __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict__ in,
                                                          void *__restrict__ out,
                                                          unsigned long long n, KtLutPack pack)
@@ -90,11 +90,11 @@ __global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict_
         uint32_t x = 0;
         if constexpr (F32) {
             if (live) x = static_cast<const uint32_t *>(in)[i];
-            x = apply_f32_one<OP>(x, tab);
+            x = apply_f32_one<OP, WIDE>(x, tab);
             if (live) static_cast<uint32_t *>(out)[i] = x;
         } else {
             if (live) x = static_cast<const uint16_t *>(in)[i];
-            x = apply_pair<OP>(x, tab);
+            x = apply_pair<OP, WIDE>(x, tab);
             if (live) static_cast<uint16_t *>(out)[i] = (uint16_t)x;
         }
     }
@@ -182,10 +182,14 @@ ktanh_status_t pack_for(const ktanh_lut64_t *lut, bool f32, KtLutPack *pack)
     return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
 }
 
+constexpr bool is_wide(const ktanh_lut_t *) { return false; }
+constexpr bool is_wide(const ktanh_lut64_t *) { return true; }
+
 template <bool F32, int OP, class Lut>
 ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut *lut,
                                   ktanh_stream_t stream)
 {
+    constexpr bool WIDE = is_wide(static_cast<const Lut *>(nullptr));
     constexpr size_t kElem = F32 ? 4 : 2;
     constexpr size_t kPerVec = 16 / kElem;
     if (n == 0) return KT_OK;
@@ -217,12 +221,12 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
         size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        hipLaunchKernelGGL((stream_kernel<F32, OP, kUnroll>), dim3((unsigned)tiles), dim3(kBlock), 0,
+        hipLaunchKernelGGL((stream_kernel<F32, OP, WIDE, kUnroll>), dim3((unsigned)tiles), dim3(kBlock), 0,
                            s, vin, vout, (unsigned long long)nvec, edge, pack);
     } else {
         const size_t want = (n + kBlock - 1) / kBlock;
         const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
-        hipLaunchKernelGGL((element_kernel<F32, OP>), dim3(blocks), dim3(kBlock), 0, s, in, out,
+        hipLaunchKernelGGL((element_kernel<F32, OP, WIDE>), dim3(blocks), dim3(kBlock), 0, s, in, out,
                            (unsigned long long)n, pack);
     }
     return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
@@ -245,13 +249,13 @@ extern "C" ktanh_status_t ktanh_f32(const uint32_t *in, uint32_t *out, size_t n,
 extern "C" ktanh_status_t ktanh64_bf16(const uint16_t *in, uint16_t *out, size_t n,
                                        const ktanh_lut64_t *lut, ktanh_stream_t stream)
 {
-    return launch_elementwise<false, OP_TANH64>(in, out, n, lut, stream);
+    return launch_elementwise<false, OP_TANH>(in, out, n, lut, stream);
 }
 
 extern "C" ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n,
                                       const ktanh_lut64_t *lut, ktanh_stream_t stream)
 {
-    return launch_elementwise<true, OP_TANH64>(in, out, n, lut, stream);
+    return launch_elementwise<true, OP_TANH>(in, out, n, lut, stream);
 }
 
 extern "C" ktanh_status_t ksigmoid(const uint16_t *in, uint16_t *out, size_t n,
@@ -268,6 +272,24 @@ extern "C" ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n,
 
 extern "C" ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n,
                                 const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_GELU>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid64(const uint16_t *in, uint16_t *out, size_t n,
+                                     const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish64(const uint16_t *in, uint16_t *out, size_t n,
+                                   const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu64(const uint16_t *in, uint16_t *out, size_t n,
+                                  const ktanh_lut64_t *lut, ktanh_stream_t stream)
 {
     return launch_elementwise<false, OP_GELU>(in, out, n, lut, stream);
 }

@@ -465,3 +465,30 @@ def test_random_valid_tables(gpu, oracle):
         assert binding.ktanh_lut64_validate(k64) == 0, rows64
         assert np.array_equal(_to_host(binding.ktanh64_bf16(xd, lut=k64), np.uint16), oracle.ktanh64_bf16(x, o64))
         assert np.array_equal(_to_host(binding.ktanh64_f32(ud, lut=k64), np.uint32), oracle.ktanh64_f32(u, o64))
+
+
+def test_derived_ops_and_lstm_on_64_interval_tables(gpu, oracle):
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(640))
+    x = np.concatenate([wl.all_bf16_patterns(), wl.mlp_preactivations(300007, seed=66)])
+    xd = _to_dev(torch, x)
+    gates, c0 = wl.lstm_cell_inputs(5, 7, 72)
+    edge = wl.edge_bf16_patterns()
+    gates.reshape(-1)[: edge.size] = edge
+    gd, cd = _to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0")
+    tables = [None, _random_valid_table(rng, 64), _random_valid_table(rng, 64)]
+    for rows in tables:
+        k64 = None if rows is None else binding.KtanhLut64.from_tuples(rows)
+        o64 = None if rows is None else oracle.OracleLut64.from_tuples(rows)
+        for name in ("ksigmoid64", "kswish64", "kgelu64"):
+            got = _to_host(getattr(binding, name)(xd, lut=k64), np.uint16)
+            with np.errstate(all="ignore"):
+                want = getattr(oracle, name)(x, o64)
+            _assert_bf16_equal(got, want, False, name)
+        c_got, h_got = binding.klstm_cell64(gd, cd, lut=k64)
+        with np.errstate(all="ignore"):
+            c_ref, h_ref = oracle.klstm_cell64(gates, c0, o64)
+        cn = np.isnan(c_ref)
+        assert np.array_equal(np.isnan(c_got.cpu().numpy()), cn)
+        assert np.array_equal(c_got.cpu().numpy().view(np.uint32)[~cn], c_ref.view(np.uint32)[~cn])
+        _assert_bf16_equal(_to_host(h_got, np.uint16).ravel(), h_ref.ravel(), False, "klstm_cell64 h")
