@@ -61,39 +61,58 @@ struct LaneTable {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Algorithm 1 on two BFloat16 magnitudes held in one register (sign bits clear, NaN not handled).
-//   slot      = low six bits of (E_i, M_i[6:4]) after clamping |x| to 4.0, so that everything
-//               beyond T2 reads the saturation slot and needs no test of its own;
-//   table out = (E_t << 7) + b_t + (M_i >> r_t).  Every slot belongs to one input exponent E_i, and
-//               (|x| >> r) = (E_i << (7 - r)) + (M_i >> r) exactly for r <= 7, so the slot stores
-//               base_t = (E_t << 7) + b_t - (E_i << (7 - r_t)) and the magnitude is shifted whole:
-//               no mantissa mask.  (The saturation slot shifts by 15, which leaves 0.)
-//   |x| < T1  = input passed through.
-__device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTable &tab)
+// Algorithm 1 on two BFloat16 magnitudes held in one register (sign bits clear, NaN not handled),
+// in two phases so that a caller with several independent pairs can put all their table reads in
+// flight before the first result is needed.
+//   32 intervals (WIDE = false)
+//     slot      = low six bits of (E_i, M_i[6:4]) after clamping |x| to 4.0, so that everything
+//                 beyond T2 reads the saturation slot and needs no test of its own;
+//     table out = (E_t << 7) + b_t + (M_i >> r_t).  Every slot belongs to one input exponent E_i,
+//                 and (|x| >> r) = (E_i << (7 - r)) + (M_i >> r) exactly for r <= 7, so the slot
+//                 stores base_t = (E_t << 7) + b_t - (E_i << (7 - r_t)) and the magnitude is
+//                 shifted whole: no mantissa mask.  (The saturation slot shifts by 15: 0 is left.)
+//     |x| < T1  = input passed through.
+//   64 intervals (WIDE = true): index = 2 low exponent bits, 4 high mantissa bits; all 64 lanes hold
+//     table entries, so saturation is a select of its own.
+struct SlotPair {
+    uint32_t key2;  // the magnitudes the slots were read for (clamped to 4.0 for 32 intervals)
+    uint32_t e_lo, e_hi;
+};
+
+template <bool WIDE>
+__device__ __forceinline__ SlotPair fetch_slots(uint32_t mag2, const LaneTable &tab)
 {
-    const uint32_t mc2 = as_u32(__builtin_elementwise_min(as_u16x2(mag2), splat(0x4080)));
-    const uint32_t e_lo = tab.get(mc2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
-    const uint32_t e_hi = tab.get(mc2 >> 18);  // same bits of the high value
-    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
-    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
-    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mc2) >> as_u16x2(r2)));
-    // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
-    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
-    return bitsel(pass, mag2, lut2);
+    SlotPair sp;
+    if constexpr (WIDE) {
+        sp.key2 = mag2;
+        sp.e_lo = tab.get(mag2 >> 1);   // bits [7:2] <- bits [8:3] of the low value
+        sp.e_hi = tab.get(mag2 >> 17);  // same bits of the high value
+    } else {
+        sp.key2 = as_u32(__builtin_elementwise_min(as_u16x2(mag2), splat(0x4080)));
+        sp.e_lo = tab.get(sp.key2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
+        sp.e_hi = tab.get(sp.key2 >> 18);  // same bits of the high value
+    }
+    return sp;
 }
 
-// The same with a 64-interval table (index = 2 low exponent bits, 4 high mantissa bits): all 64
-// lanes hold table entries, so saturation is a select of its own.
-__device__ __forceinline__ uint32_t ktanh64_mag_pair(uint32_t mag2, const LaneTable &tab)
+template <bool WIDE>
+__device__ __forceinline__ uint32_t finish_mag_pair(uint32_t mag2, const SlotPair &sp)
 {
-    const uint32_t e_lo = tab.get(mag2 >> 1);   // bits [7:2] <- bits [8:3] of the low value
-    const uint32_t e_hi = tab.get(mag2 >> 17);  // same bits of the high value
-    const uint32_t base2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x07060302u);
-    const uint32_t r2 = __builtin_amdgcn_perm(e_hi, e_lo, 0x05040100u);
-    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(mag2) >> as_u16x2(r2)));
+    const uint32_t base2 = __builtin_amdgcn_perm(sp.e_hi, sp.e_lo, 0x07060302u);
+    const uint32_t r2 = __builtin_amdgcn_perm(sp.e_hi, sp.e_lo, 0x05040100u);
+    const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(sp.key2) >> as_u16x2(r2)));
+    // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
     const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    const uint32_t res = bitsel(pass, mag2, lut2);
+    if constexpr (!WIDE) return res;
     const uint32_t beyond = sign_mask_pair(as_u32(as_i16x2(0x407F407Fu) - as_i16x2(mag2)));
-    return bitsel(beyond, 0x3F803F80u, bitsel(pass, mag2, lut2));
+    return bitsel(beyond, 0x3F803F80u, res);
+}
+
+template <bool WIDE = false>
+__device__ __forceinline__ uint32_t ktanh_mag_pair(uint32_t mag2, const LaneTable &tab)
+{
+    return finish_mag_pair<WIDE>(mag2, fetch_slots<WIDE>(mag2, tab));
 }
 
 // 0xFFFF in each half that holds a NaN magnitude (> 0x7F80).
@@ -109,7 +128,7 @@ __device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
 {
     const uint32_t mag2 = w & kMag2;
     const uint32_t res =
-        bitsel(kMag2, WIDE ? ktanh64_mag_pair(mag2, tab) : ktanh_mag_pair(mag2, tab), w);
+        bitsel(kMag2, ktanh_mag_pair<WIDE>(mag2, tab), w);
     if constexpr (!NANS) return res;
     return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
 }
@@ -153,23 +172,35 @@ __device__ __forceinline__ uint32_t narrow_pair(float lo, float hi)
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// 0.5 * K(0.5 x) + 0.5 in Float32 for both halves of w.
+// Sigmoid: 0.5 * K(0.5 x) + 0.5 in Float32 for both halves of w, in three pieces.
 //   Halving a BFloat16 is "exponent field minus one" whenever that field is at least 2; below that
 //   |x| < 2^-125, K passes its argument through and the result is 0.5 whatever the argument, so a
 //   saturating subtract of 0x80 from the magnitude stands for the multiply and the rounding.
 //   0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse.
+//
+// Magnitudes of x/2 for both halves of w (the argument of K inside the Sigmoid).
+__device__ __forceinline__ uint32_t sigmoid_half_mag_pair(uint32_t w)
+{
+    return as_u32(__builtin_elementwise_sub_sat(as_u16x2(w & kMag2), splat(0x0080)));
+}
+
+// 0.5 * t + 0.5 for both halves, t = the K output magnitudes `t_mag2` with the signs of w.
+template <bool NANS>
+__device__ __forceinline__ void sigmoid_from_ktanh_pair(uint32_t w, uint32_t t_mag2, float &s_lo,
+                                                        float &s_hi)
+{
+    uint32_t t2 = bitsel(kMag2, t_mag2, w);
+    if constexpr (NANS)
+        t2 = bitsel(nan_mask_pair(w & kMag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
+    s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
+    s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+}
+
 template <bool NANS = true, bool WIDE = false>
 __device__ __forceinline__ void ksigmoid_f32_pair(uint32_t w, const LaneTable &tab, float &s_lo,
                                                   float &s_hi)
 {
-    const uint32_t mag2 = w & kMag2;
-    const uint32_t half_mag2 = as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x0080)));
-    uint32_t t2 = bitsel(
-        kMag2, WIDE ? ktanh64_mag_pair(half_mag2, tab) : ktanh_mag_pair(half_mag2, tab), w);
-    if constexpr (NANS)
-        t2 = bitsel(nan_mask_pair(mag2), w | 0x00400040u, t2);  // NaN in -> NaN through the sums
-    s_lo = __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
-    s_hi = __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
+    sigmoid_from_ktanh_pair<NANS>(w, ktanh_mag_pair<WIDE>(sigmoid_half_mag_pair(w), tab), s_lo, s_hi);
 }
 
 // 128-bit streaming accesses: every byte is touched once.  Measured on tensors that come from HBM:
