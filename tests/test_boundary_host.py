@@ -153,3 +153,19 @@ def test_host_sources_under_address_and_ub_sanitizers(tmp_path):
     res = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
     assert res.returncode == 0, res.stdout + res.stderr
     assert "host sources clean" in res.stdout
+
+
+def test_sizes_beyond_the_grid_limit_are_rejected_on_the_host(binding):
+    """A grid holds at most 2^31 - 1 single-wavefront blocks; larger tensors are refused (status 4)
+    before anything is launched, so fake pointers are never touched."""
+    lib = binding.load_library()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "ktanh64_bf16"):
+        assert getattr(lib, name)(fake, fake, (1 << 40) + 8, None, null) == 4
+        assert getattr(lib, name)(fake, fake, 1 << 40, None, null) == 4      # 2^31 blocks: one too many
+    for name in ("ktanh_f32", "ksigmoid_f32", "ktanh_f32_to_bf16", "ktanh64_f32"):
+        assert getattr(lib, name)(fake, fake, 1 << 39, None, null) == 4
+    # LSTM cell: B * H / 2 lane pairs must stay below 2^28; T below 2^31
+    assert lib.klstm_cell(fake, fake, fake, fake, 1, 1 << 20, 1 << 9, None, null) == 4
+    assert lib.klstm_cell(fake, fake, fake, fake, 1 << 31, 1, 8, None, null) == 4
+    assert lib.klstm_cell64(fake, fake, fake, fake, 1, 1 << 20, 1 << 9, None, null) == 4
