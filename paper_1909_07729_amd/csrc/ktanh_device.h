@@ -297,4 +297,20 @@ __device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
                  apply_f32_one<OP, WIDE>(v.z, tab), apply_f32_one<OP, WIDE>(v.w, tab)};
 }
 
+// Enqueues `kernel` and returns the status of this very launch (the launch macro would only leave it
+// in the runtime's last-error slot, next to whatever an earlier, unrelated call left there).
+template <class... Params, class... Args>
+inline ktanh_status_t launch_checked(void (*kernel)(Params...), unsigned blocks, unsigned threads,
+                                     ktanh_stream_t stream, Args... args)
+{
+    static_assert(sizeof...(Params) == sizeof...(Args), "argument count");
+    // each argument converted to the kernel's parameter type, then passed by address
+    auto call = [&](Params... converted) {
+        void *slots[] = {static_cast<void *>(&converted)...};
+        return hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(threads),
+                               slots, 0, static_cast<hipStream_t>(stream));
+    };
+    return call(args...) == hipSuccess ? KT_OK : KT_ERR_HIP;
+}
+
 }  // namespace ktanh_device

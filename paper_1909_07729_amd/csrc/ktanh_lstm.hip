@@ -168,12 +168,11 @@ ktanh_status_t launch_cell(const uint16_t *gates, const float *c_in, float *c_ou
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
     if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
     const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
-    hipLaunchKernelGGL(lstm_cell_kernel<WIDE>, dim3((unsigned)blocks), dim3(kCellBlock), 0,
-                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(gates),
-                       reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
-                       reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
-                       (unsigned)(H / 2), !within_unit, pack);
-    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+    return launch_checked(lstm_cell_kernel<WIDE>, (unsigned)blocks, kCellBlock, stream,
+                          reinterpret_cast<const uint32_t *>(gates),
+                          reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
+                          reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
+                          (unsigned)(H / 2), !within_unit, pack);
 }
 
 }  // namespace

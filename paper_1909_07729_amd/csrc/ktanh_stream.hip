@@ -201,7 +201,6 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
     const ktanh_status_t st = pack_for(lut, F32, &pack);
     if (st != KT_OK) return st;
 
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned max_blocks = (unsigned)compute_units() * kBlocksPerCu;
 
     if ((ain & 15) == (aout & 15)) {
@@ -221,15 +220,13 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
         size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        hipLaunchKernelGGL((stream_kernel<F32, OP, WIDE, kUnroll>), dim3((unsigned)tiles), dim3(kBlock), 0,
-                           s, vin, vout, (unsigned long long)nvec, edge, pack);
-    } else {
-        const size_t want = (n + kBlock - 1) / kBlock;
-        const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
-        hipLaunchKernelGGL((element_kernel<F32, OP, WIDE>), dim3(blocks), dim3(kBlock), 0, s, in, out,
-                           (unsigned long long)n, pack);
+        return launch_checked(stream_kernel<F32, OP, WIDE, kUnroll>, (unsigned)tiles, kBlock, stream,
+                              vin, vout, (unsigned long long)nvec, edge, pack);
     }
-    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+    const size_t want = (n + kBlock - 1) / kBlock;
+    const unsigned blocks = (unsigned)(want < max_blocks ? want : max_blocks);
+    return launch_checked(element_kernel<F32, OP, WIDE>, blocks, kBlock, stream, in, out,
+                          (unsigned long long)n, pack);
 }
 
 }  // namespace
@@ -323,7 +320,6 @@ extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size
     KtLutPack pack;
     const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
     if (st != KT_OK) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
 
     size_t head = ((16 - (ain & 15)) & 15) / 4;  // elements until `in` is 16-byte aligned
     if (head > n) head = n;
@@ -339,15 +335,14 @@ extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size
         size_t tiles = (nvec + kBlock - 1) / kBlock;
         if (tiles == 0) tiles = 1;
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        hipLaunchKernelGGL(narrow_stream_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, s,
-                           reinterpret_cast<const uint4 *>(in + head),
-                           reinterpret_cast<uint2 *>(out + head), (unsigned long long)nvec, edge, pack);
-    } else {
-        const size_t want = (n + kBlock - 1) / kBlock;
-        const size_t max_blocks = (size_t)compute_units() * kBlocksPerCu;
-        hipLaunchKernelGGL(narrow_element_kernel, dim3((unsigned)(want < max_blocks ? want : max_blocks)),
-                           dim3(kBlock), 0, s, reinterpret_cast<const uint32_t *>(in), out,
-                           (unsigned long long)n, pack);
+        return launch_checked(narrow_stream_kernel, (unsigned)tiles, kBlock, stream,
+                              reinterpret_cast<const uint4 *>(in + head),
+                              reinterpret_cast<uint2 *>(out + head), (unsigned long long)nvec, edge,
+                              pack);
     }
-    return hipGetLastError() == hipSuccess ? KT_OK : KT_ERR_HIP;
+    const size_t want = (n + kBlock - 1) / kBlock;
+    const size_t max_blocks = (size_t)compute_units() * kBlocksPerCu;
+    return launch_checked(narrow_element_kernel, (unsigned)(want < max_blocks ? want : max_blocks),
+                          kBlock, stream, reinterpret_cast<const uint32_t *>(in), out,
+                          (unsigned long long)n, pack);
 }
