@@ -29,6 +29,14 @@
  *                          prints nothing for these: pinned through the
  *                          BFloat16 operations where the two must coincide,
  *                          and by double-precision re-evaluation)
+ *   oracle_ktanh_backward, oracle_ksigmoid_backward, oracle_klstm_cell_backward
+ *                          gradients for training through K-TanH (Section 3
+ *                          trains GNMT with it; the paper does not say how
+ *                          the gradient is formed): the derivative identities
+ *                          of TanH and Sigmoid, dy*(1-y^2) and dy*s*(1-s),
+ *                          evaluated on the K-TanH outputs.  Parity unpinned by
+ *                          the paper; pinned by double re-evaluation, by the
+ *                          distance to the exact derivatives, and by hand
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
@@ -484,4 +492,83 @@ void oracle_kgelu_f32(const float *in, float *out, size_t n, const oracle_lut *l
 void oracle_ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n, const oracle_lut *lut)
 {
     for (size_t i = 0; i < n; ++i) out[i] = ktanh_bf16_scalar(narrow_rne(in[i]), lut);
+}
+
+/* ------------------------------------------------------------------ */
+/* Gradients.  Float32 arithmetic, one rounding per written operation. */
+
+/* dx = dy * (1 - y*y), y = the forward K-TanH output. */
+void oracle_ktanh_backward(const uint16_t *dy, const uint16_t *y, uint16_t *dx, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float yv = widen(y[i]);
+        float y2 = yv * yv;
+        float slope = 1.0f - y2;
+        float g = widen(dy[i]) * slope;
+        dx[i] = narrow_rne(g);
+    }
+}
+
+/* dx = dy * (s * (1 - s)), s = the forward Sigmoid output. */
+void oracle_ksigmoid_backward(const uint16_t *dy, const uint16_t *sg, uint16_t *dx, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float sv = widen(sg[i]);
+        float one_minus = 1.0f - sv;
+        float slope = sv * one_minus;
+        float g = widen(dy[i]) * slope;
+        dx[i] = narrow_rne(g);
+    }
+}
+
+/* One LSTM-cell step backwards.  The forward activations are recomputed from
+ * the gate pre-activations with K-TanH, exactly as oracle_klstm_cell forms them.
+ *   gates   [B][4H] BFloat16 (i|f|g|o)      c_prev  [B][H] Float32
+ *   dh      [B][H]  BFloat16                dc_next [B][H] Float32
+ *   dgates  [B][4H] BFloat16 (out)          dc_prev [B][H] Float32 (out)
+ * With c' = f*c + i*g, tc = K(bf16(c')), h = o*tc:
+ *   do = dh*tc                dc = dc_next + (dh*o)*(1 - tc*tc)
+ *   di = dc*g   df = dc*c_prev   dg = dc*i   dc_prev = dc*f
+ *   d(gate pre-activations) = di*(i*(1-i)) | df*(f*(1-f)) | dg*(1 - g*g) | do*(o*(1-o)) */
+void oracle_klstm_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                size_t H, const oracle_lut *lut)
+{
+    for (size_t bi = 0; bi < B; ++bi) {
+        const uint16_t *row = gates + bi * 4 * H;
+        uint16_t *drow = dgates + bi * 4 * H;
+        for (size_t j = 0; j < H; ++j) {
+            float ig = ksigmoid_f32_of_bf16(row[0 * H + j], lut);
+            float fg = ksigmoid_f32_of_bf16(row[1 * H + j], lut);
+            float gg = widen(ktanh_bf16_scalar(row[2 * H + j], lut));
+            float og = ksigmoid_f32_of_bf16(row[3 * H + j], lut);
+            float c0 = c_prev[bi * H + j];
+            float keep = fg * c0;
+            float add = ig * gg;
+            float c1 = keep + add;
+            float tc = widen(ktanh_bf16_scalar(narrow_rne(c1), lut));
+            float dhv = widen(dh[bi * H + j]);
+
+            float d_o = dhv * tc;
+            float dh_o = dhv * og;
+            float tc2 = tc * tc;
+            float tslope = 1.0f - tc2;
+            float through = dh_o * tslope;
+            float dc = dc_next[bi * H + j] + through;
+
+            float d_i = dc * gg;
+            float d_f = dc * c0;
+            float d_g = dc * ig;
+            dc_prev[bi * H + j] = dc * fg;
+
+            float i1 = 1.0f - ig, f1 = 1.0f - fg, o1 = 1.0f - og;
+            float islope = ig * i1, fslope = fg * f1, oslope = og * o1;
+            float g2 = gg * gg;
+            float gslope = 1.0f - g2;
+            drow[0 * H + j] = narrow_rne(d_i * islope);
+            drow[1 * H + j] = narrow_rne(d_f * fslope);
+            drow[2 * H + j] = narrow_rne(d_g * gslope);
+            drow[3 * H + j] = narrow_rne(d_o * oslope);
+        }
+    }
 }

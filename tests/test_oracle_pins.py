@@ -505,3 +505,69 @@ def test_derived_ops_on_64_interval_tables(oracle):
     c_a, h_a = oracle.klstm_cell64(gates, c0, doubled)
     c_b, h_b = oracle.klstm_cell(gates, c0)
     assert np.array_equal(c_a, c_b) and np.array_equal(h_a, h_b)
+
+
+# ---------------------------------------------------------------- gradients
+def test_backward_of_ktanh_and_ksigmoid(oracle):
+    """dy * (1 - y^2) and dy * s * (1 - s) on the forward outputs: float64 re-evaluation to 1 ulp,
+    the distance to the exact derivatives bounded by the forward error, and two values by hand."""
+    x = _finite_bf16()
+    rng = np.random.Generator(np.random.PCG64(33))
+    dy = wl.f32_to_bf16_bits(rng.standard_normal(x.size, dtype=np.float32))
+    y, s = oracle.ktanh_bf16(x), oracle.ksigmoid(x)
+    yv, sv, dv = _bf16_val(y), _bf16_val(s), _bf16_val(dy)
+    assert np.max(_ulp_distance_bf16(oracle.ktanh_backward(dy, y), _round_f64_to_bf16(dv * (1 - yv * yv)))) <= 1
+    assert np.max(_ulp_distance_bf16(oracle.ksigmoid_backward(dy, s), _round_f64_to_bf16(dv * sv * (1 - sv)))) <= 1
+    ones = np.full(x.size, 0x3F80, dtype=np.uint16)
+    xv = _bf16_val(x)
+    slope = _bf16_val(oracle.ktanh_backward(ones, y))
+    assert np.max(np.abs(slope - (1 - np.tanh(xv) ** 2))) <= 2 * 1.67e-2 + 2.0 ** -8
+    sl = _bf16_val(oracle.ksigmoid_backward(ones, s))
+    true_s = 1 / (1 + np.exp(-xv.clip(-80, 80)))
+    assert np.max(np.abs(sl - true_s * (1 - true_s))) <= 1.67e-2 / 2 + 2.0 ** -9
+    # y = K(1.0) = 0x3F41 = 193/256: 1 - y^2 = 28287/65536 = 1.7265 * 2^-2 -> mantissa 92.99 -> 93
+    assert oracle.ktanh_backward(np.array([0x3F80], np.uint16), np.array([0x3F41], np.uint16))[0] == 0x3EDD
+    # s = 0.75, dy = 2: 2 * 0.75 * 0.25 = 0.375 = 0x3EC0
+    assert oracle.ksigmoid_backward(np.array([0x4000], np.uint16), np.array([0x3F40], np.uint16))[0] == 0x3EC0
+
+
+def test_lstm_cell_backward(oracle):
+    """By hand: gates 0, c = 1, dh = 1, dc_next = 0 -> i = f = o = 0.5, g = 0, c' = 0.5,
+    tc = K(0.5) = 0.46875; do = 0.46875, dc = 0.5 * (1 - tc^2) = 0.39013671875;
+    dgates = (0, dc*1*0.25, dc*0.5*1, 0.46875*0.25), dc_prev = dc * 0.5."""
+    H = 8
+    gates = np.zeros((1, 4 * H), np.uint16)
+    dg, dcp = oracle.klstm_cell_backward(gates, np.ones((1, H), np.float32), np.full((1, H), 0x3F80, np.uint16),
+                                         np.zeros((1, H), np.float32))
+    assert np.all(dg[0, :H] == 0x0000) and np.all(dg[0, H:2 * H] == 0x3DC8)
+    assert np.all(dg[0, 2 * H:3 * H] == 0x3E48) and np.all(dg[0, 3 * H:] == 0x3DF0)
+    assert np.all(dcp == np.float32(0.195068359375))
+
+    # float64 re-evaluation around the pinned forward pieces, and against an exact-tanh LSTM
+    B, H = 6, 32
+    g3, c0 = wl.lstm_cell_inputs(1, B, H)
+    gates = g3[0]
+    rng = np.random.Generator(np.random.PCG64(34))
+    dh = wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32))
+    dcn = rng.standard_normal((B, H), dtype=np.float32)
+    dg, dcp = oracle.klstm_cell_backward(gates, c0, dh, dcn)
+    g4 = gates.reshape(B, 4, H)
+    sig = lambda bits: (1.0 + _bf16_val(oracle.ktanh_bf16(_round_f64_to_bf16(_bf16_val(bits) / 2)))) / 2
+    i, f, o, g = sig(g4[:, 0]), sig(g4[:, 1]), sig(g4[:, 3]), _bf16_val(oracle.ktanh_bf16(g4[:, 2]))
+    c1, _ = oracle.klstm_cell(g3, c0)
+    tc = _bf16_val(oracle.ktanh_bf16(wl.f32_to_bf16_bits(c1)))
+    dhv = _bf16_val(dh)
+    dc = dcn.astype(np.float64) + dhv * o * (1 - tc * tc)
+    want = np.stack([dc * g * i * (1 - i), dc * c0 * f * (1 - f), dc * i * (1 - g * g), dhv * tc * o * (1 - o)], axis=1)
+    got = _bf16_val(dg.reshape(B, 4, H))
+    assert np.max(np.abs(got - want) - 2.0 ** -8 * np.abs(want)) <= 1e-6
+    assert np.max(np.abs(dcp - dc * f)) <= 1e-6 * (1 + np.max(np.abs(dc)))
+    # the same formulas with exact tanh / sigmoid: close, since K is close
+    x4 = _bf16_val(g4)
+    ei, ef, eo = [1 / (1 + np.exp(-x4[:, k])) for k in (0, 1, 3)]
+    eg = np.tanh(x4[:, 2])
+    ec1 = ef * c0 + ei * eg
+    etc = np.tanh(ec1)
+    edc = dcn + dhv * eo * (1 - etc ** 2)
+    exact = np.stack([edc * eg * ei * (1 - ei), edc * c0 * ef * (1 - ef), edc * ei * (1 - eg ** 2), dhv * etc * eo * (1 - eo)], axis=1)
+    assert np.max(np.abs(got - exact)) <= 0.15 and np.mean(np.abs(got - exact)) <= 0.01
