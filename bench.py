@@ -179,6 +179,10 @@ def run_extras(torch, binding, wl, upload, xs, ys):
     record("ktanh64_bf16", "[50,128,4096] bf16 as in the headline, 64-interval table, 8 rotating buffer pairs",
            lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
 
+    record("ktanh_bf16_backward", "dy, y and dx as the headline tensor (6 B per element), 8 rotating triples",
+           lambda i: binding.ktanh_bf16_backward(xs[i % ROTATE], ys[(i + 1) % ROTATE], dx=ys[i % ROTATE]),
+           xs[0].numel(), 6, 2000, 500)
+
     # the large tensors rotate as well: a 537 MB working set still keeps part of itself in the cache
     x4 = [upload(wl.mlp_preactivations())]
     for k in range(1, 4):

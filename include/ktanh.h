@@ -182,6 +182,32 @@ ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out
                           size_t T, size_t B, size_t H, const ktanh_lut_t *lut,
                           ktanh_stream_t stream);
 
+/* ---- Gradients ------------------------------------------------------------------------------------
+ * Section 3 trains GNMT through K-TanH; the paper does not say how the gradient is formed.  These
+ * entry points use the derivative identities of TanH and Sigmoid on the forward outputs:
+ *   ktanh_bf16_backward:  dx = bf16( dy * (1 - y*y) ),      y = forward K-TanH output
+ *   ksigmoid_backward:    dx = bf16( dy * (s * (1 - s)) ),  s = forward Sigmoid output
+ * BFloat16 tensors of n elements, device; Float32 arithmetic, one rounding per operation, result
+ * rounded to nearest even.  dx may alias dy or the forward output.  No table is involved. */
+ktanh_status_t ktanh_bf16_backward(const uint16_t *dy, const uint16_t *y, uint16_t *dx, size_t n,
+                                   ktanh_stream_t stream);
+ktanh_status_t ksigmoid_backward(const uint16_t *dy, const uint16_t *s, uint16_t *dx, size_t n,
+                                 ktanh_stream_t stream);
+
+/* One klstm_cell step backwards.  The forward activations are recomputed from the gate
+ * pre-activations with K-TanH exactly as klstm_cell forms them (i, f, o, g, c' = f*c + i*g,
+ * tc = K(bf16(c'))); then, in Float32, one rounding per operation:
+ *   do = dh*tc;   dc = dc_next + (dh*o)*(1 - tc*tc);
+ *   di = dc*g;  df = dc*c_prev;  dg = dc*i;  dc_prev = dc*f;
+ *   dgates = bf16( di*(i*(1-i)) | df*(f*(1-f)) | dg*(1 - g*g) | do*(o*(1-o)) )
+ *   gates   [B][4H] BFloat16 (i|f|g|o), device     c_prev  [B][H] Float32, device
+ *   dh      [B][H]  BFloat16, device               dc_next [B][H] Float32, device
+ *   dgates  [B][4H] BFloat16, device, out          dc_prev [B][H] Float32, device, out (may be dc_next)
+ * H must be a multiple of 8 (KT_ERR_SHAPE); all tensors 16-byte aligned (KT_ERR_ALIGN). */
+ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                   const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                   size_t H, const ktanh_lut_t *lut, ktanh_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

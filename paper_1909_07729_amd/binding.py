@@ -20,7 +20,8 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell",
            "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32",
            "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
-           "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64")
+           "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
+           "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward")
 
 
 class KtanhLut(ctypes.Structure):
@@ -110,6 +111,12 @@ def load_library() -> ctypes.CDLL:
             fn.restype = ctypes.c_int
         lib.klstm_cell64.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp64, vp]
         lib.klstm_cell64.restype = ctypes.c_int
+        for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, vp, sz, vp]
+            fn.restype = ctypes.c_int
+        lib.klstm_cell_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz, lp, vp]
+        lib.klstm_cell_backward.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -292,3 +299,57 @@ def klstm_cell(gates, c_in, c_out=None, h_out=None, lut=None, stream=None, _entr
     if st != 0:
         raise KtanhError(st, _entry)
     return c_out, h_out
+
+
+def _backward(name, dy, fwd, dx, stream):
+    _check(dy, _BF16_VIEWS, "dy")
+    _check(fwd, _BF16_VIEWS, "forward output")
+    if dx is None:
+        dx = torch.empty_like(dy)
+    _check(dx, _BF16_VIEWS, "dx")
+    if not (dy.numel() == fwd.numel() == dx.numel()):
+        raise ValueError("dy, the forward output and dx differ in size")
+    st = getattr(load_library(), name)(dy.data_ptr(), fwd.data_ptr(), dx.data_ptr(), dy.numel(),
+                                       _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, name)
+    return dx
+
+
+def ktanh_bf16_backward(dy, y, dx=None, stream=None):
+    """dx = dy * (1 - y^2) from the forward K-TanH output y (BFloat16 tensors)."""
+    return _backward("ktanh_bf16_backward", dy, y, dx, stream)
+
+
+def ksigmoid_backward(dy, s, dx=None, stream=None):
+    """dx = dy * s * (1 - s) from the forward Sigmoid output s (BFloat16 tensors)."""
+    return _backward("ksigmoid_backward", dy, s, dx, stream)
+
+
+def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None):
+    """One LSTM-cell step backwards.  gates [B, 4H] BFloat16, c_prev and dc_next [B, H] Float32,
+    dh [B, H] BFloat16.  Returns (dgates [B, 4H], dc_prev [B, H])."""
+    _check(gates, _BF16_VIEWS, "gates")
+    _check(dh, _BF16_VIEWS, "dh")
+    _check(c_prev, (torch.float32,), "c_prev")
+    _check(dc_next, (torch.float32,), "dc_next")
+    if gates.dim() != 2:
+        raise ValueError("gates must be [B, 4H]")
+    B, H4 = gates.shape
+    H = H4 // 4
+    if H4 != 4 * H or not (tuple(c_prev.shape) == tuple(dh.shape) == tuple(dc_next.shape) == (B, H)):
+        raise ValueError("gates [B, 4H], c_prev, dh, dc_next [B, H] do not agree")
+    if dgates is None:
+        dgates = torch.empty_like(gates)
+    if dc_prev is None:
+        dc_prev = torch.empty_like(c_prev)
+    _check(dgates, _BF16_VIEWS, "dgates")
+    _check(dc_prev, (torch.float32,), "dc_prev")
+    if tuple(dgates.shape) != (B, H4) or tuple(dc_prev.shape) != (B, H):
+        raise ValueError("dgates must be [B, 4H] and dc_prev [B, H]")
+    st = load_library().klstm_cell_backward(gates.data_ptr(), c_prev.data_ptr(), dh.data_ptr(),
+                                            dc_next.data_ptr(), dgates.data_ptr(), dc_prev.data_ptr(),
+                                            B, H, _lut_arg(lut), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "klstm_cell_backward")
+    return dgates, dc_prev

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libktanh.so")
-SOURCES = ["ktanh_stream.hip", "ktanh_lstm.hip", "ktanh_lut.cpp", "ktanh_fit.cpp"]
+SOURCES = ["ktanh_stream.hip", "ktanh_lstm.hip", "ktanh_backward.hip", "ktanh_lut.cpp", "ktanh_fit.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-std=c++17", "-O3", "-fPIC", "-shared",

@@ -1,0 +1,209 @@
+// libktanh: gradients for training through K-TanH -- the derivative identities of TanH and Sigmoid
+// on the forward outputs, and one LSTM-cell step backwards -- and their entry points.
+#include "ktanh_device.h"
+
+using namespace ktanh_device;
+
+namespace {
+
+enum Grad { GRAD_TANH = 0, GRAD_SIGMOID = 1 };
+
+// dy * slope(forward output) for both halves of a packed pair.
+template <int GRAD>
+__device__ __forceinline__ uint32_t grad_pair(uint32_t dy2, uint32_t fwd2)
+{
+    float out[2];
+    const float dy[2] = {widen_lo(dy2), widen_hi(dy2)};
+    const float v[2] = {widen_lo(fwd2), widen_hi(fwd2)};
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        float slope;
+        if constexpr (GRAD == GRAD_TANH) {
+            const float sq = v[k] * v[k];
+            slope = 1.0f - sq;
+        } else {
+            const float one_minus = 1.0f - v[k];
+            slope = v[k] * one_minus;
+        }
+        out[k] = dy[k] * slope;
+    }
+    return narrow_pair(out[0], out[1]);
+}
+
+// Two BFloat16 input streams, one output stream (which may be one of the inputs): 6 bytes per element.  One wavefront per block,
+// one 128-bit vector per lane; the last block also takes the n % 8 loose elements.
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_stream_kernel(const uint4 *vdy,
+                                                             const uint4 *vfwd,
+                                                             uint4 *vdx,
+                                                             unsigned long long nvec,
+                                                             const uint16_t *dy, const uint16_t *fwd,
+                                                             uint16_t *dx, unsigned long long n)
+{
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    if (at < nvec) {
+        const uint4 a = load_stream(vdy + at), b = load_stream(vfwd + at);
+        store_stream(vdx + at, uint4{grad_pair<GRAD>(a.x, b.x), grad_pair<GRAD>(a.y, b.y),
+                                     grad_pair<GRAD>(a.z, b.z), grad_pair<GRAD>(a.w, b.w)});
+    }
+    const unsigned long long loose = nvec * 8 + threadIdx.x;
+    if (blockIdx.x == gridDim.x - 1 && loose < n) dx[loose] = (uint16_t)grad_pair<GRAD>(dy[loose], fwd[loose]);
+}
+
+// Any alignment: one element per lane and pass.
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_element_kernel(const uint16_t *dy,
+                                                              const uint16_t *fwd,
+                                                              uint16_t *dx,
+                                                              unsigned long long n)
+{
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long i = (unsigned long long)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride)
+        dx[i] = (uint16_t)grad_pair<GRAD>(dy[i], fwd[i]);
+}
+
+template <int GRAD>
+ktanh_status_t launch_grad(const uint16_t *dy, const uint16_t *fwd, uint16_t *dx, size_t n,
+                           ktanh_stream_t stream)
+{
+    if (n == 0) return KT_OK;
+    if (dy == nullptr || fwd == nullptr || dx == nullptr) return KT_ERR_NULL;
+    const uintptr_t all = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(fwd) |
+                          reinterpret_cast<uintptr_t>(dx);
+    if (all & 1) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
+    if ((all & 15) == 0) {
+        const size_t nvec = n / 8;
+        size_t tiles = (nvec + kBlock - 1) / kBlock;
+        if (tiles == 0) tiles = 1;
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+        return launch_checked(grad_stream_kernel<GRAD>, (unsigned)tiles, kBlock, stream,
+                              reinterpret_cast<const uint4 *>(dy), reinterpret_cast<const uint4 *>(fwd),
+                              reinterpret_cast<uint4 *>(dx), (unsigned long long)nvec, dy, fwd, dx,
+                              (unsigned long long)n);
+    }
+    const size_t want = (n + kBlock - 1) / kBlock;
+    return launch_checked(grad_element_kernel<GRAD>, (unsigned)(want < 8192 ? want : 8192), kBlock,
+                          stream, dy, fwd, dx, (unsigned long long)n);
+}
+
+// ---------------------------------------------------------------------------------------------
+// LSTM cell, one step backwards: each lane owns two neighbouring cells (one packed pair per gate).
+// The forward activations are rebuilt with the same device functions the forward kernel uses; the
+// table reads need every lane enabled, so bounds predicate only the memory accesses.
+constexpr int kCellBlock = 256;
+
+__global__ __launch_bounds__(kCellBlock) void lstm_cell_backward_kernel(
+    const uint32_t *__restrict__ gates, const float2 *__restrict__ c_prev,
+    const uint32_t *__restrict__ dh, const float2 *dc_next, uint32_t *__restrict__ dgates,
+    float2 *dc_prev, unsigned n_pairs, unsigned H2, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned p = blockIdx.x * kCellBlock + threadIdx.x;
+    const bool live = p < n_pairs;
+    const unsigned b = live ? p / H2 : 0;
+    const unsigned j = live ? p % H2 : 0;
+    const unsigned at = b * 4u * H2 + j;  // word index of the i-gate pair inside [B][4H]
+
+    uint32_t wi = 0, wf = 0, wg = 0, wo = 0, wdh = 0;
+    float2 c0 = float2{0.f, 0.f}, dcn = float2{0.f, 0.f};
+    if (live) {
+        wi = gates[at];
+        wf = gates[at + H2];
+        wg = gates[at + 2u * H2];
+        wo = gates[at + 3u * H2];
+        wdh = dh[p];
+        c0 = c_prev[p];
+        dcn = dc_next[p];
+    }
+
+    float ig[2], fg[2], og[2];
+    ksigmoid_f32_pair(wi, tab, ig[0], ig[1]);
+    ksigmoid_f32_pair(wf, tab, fg[0], fg[1]);
+    ksigmoid_f32_pair(wo, tab, og[0], og[1]);
+    const uint32_t g2 = ktanh_pair(wg, tab);
+    const float gg[2] = {widen_lo(g2), widen_hi(g2)};
+    const float cp[2] = {c0.x, c0.y};
+    float c1[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float keep = fg[k] * cp[k], add = ig[k] * gg[k];
+        c1[k] = keep + add;
+    }
+    const uint32_t tc2 = ktanh_pair(narrow_pair(c1[0], c1[1]), tab);
+    const float tc[2] = {widen_lo(tc2), widen_hi(tc2)};
+    const float dhv[2] = {widen_lo(wdh), widen_hi(wdh)};
+    const float dnx[2] = {dcn.x, dcn.y};
+
+    float d_gi[2], d_gf[2], d_gg[2], d_go[2], dcp[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float d_o = dhv[k] * tc[k];
+        const float dh_o = dhv[k] * og[k];
+        const float tsq = tc[k] * tc[k];
+        const float tslope = 1.0f - tsq;
+        const float through = dh_o * tslope;
+        const float dc = dnx[k] + through;
+        const float d_i = dc * gg[k], d_f = dc * cp[k], d_g = dc * ig[k];
+        dcp[k] = dc * fg[k];
+        const float i1 = 1.0f - ig[k], f1 = 1.0f - fg[k], o1 = 1.0f - og[k];
+        const float islope = ig[k] * i1, fslope = fg[k] * f1, oslope = og[k] * o1;
+        const float gsq = gg[k] * gg[k];
+        const float gslope = 1.0f - gsq;
+        d_gi[k] = d_i * islope;
+        d_gf[k] = d_f * fslope;
+        d_gg[k] = d_g * gslope;
+        d_go[k] = d_o * oslope;
+    }
+    if (live) {
+        dgates[at] = narrow_pair(d_gi[0], d_gi[1]);
+        dgates[at + H2] = narrow_pair(d_gf[0], d_gf[1]);
+        dgates[at + 2u * H2] = narrow_pair(d_gg[0], d_gg[1]);
+        dgates[at + 3u * H2] = narrow_pair(d_go[0], d_go[1]);
+        dc_prev[p] = float2{dcp[0], dcp[1]};
+    }
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t ktanh_bf16_backward(const uint16_t *dy, const uint16_t *y, uint16_t *dx,
+                                              size_t n, ktanh_stream_t stream)
+{
+    return launch_grad<GRAD_TANH>(dy, y, dx, n, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid_backward(const uint16_t *dy, const uint16_t *s, uint16_t *dx,
+                                            size_t n, ktanh_stream_t stream)
+{
+    return launch_grad<GRAD_SIGMOID>(dy, s, dx, n, stream);
+}
+
+extern "C" ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev,
+                                              const uint16_t *dh, const float *dc_next,
+                                              uint16_t *dgates, float *dc_prev, size_t B, size_t H,
+                                              const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (B == 0 || H == 0) return KT_OK;
+    if (gates == nullptr || c_prev == nullptr || dh == nullptr || dc_next == nullptr ||
+        dgates == nullptr || dc_prev == nullptr)
+        return KT_ERR_NULL;
+    if (H % 8 != 0) return KT_ERR_SHAPE;
+    if (B > ((size_t)1 << 40) || H > ((size_t)1 << 40)) return KT_ERR_SHAPE;
+    const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_prev) |
+                          reinterpret_cast<uintptr_t>(dh) | reinterpret_cast<uintptr_t>(dc_next) |
+                          reinterpret_cast<uintptr_t>(dgates) | reinterpret_cast<uintptr_t>(dc_prev);
+    if (mis & 15) return KT_ERR_ALIGN;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    if (st != KT_OK) return st;
+    const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
+    if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // word indices inside [B][4H] fit 32 bits
+    const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
+    return launch_checked(lstm_cell_backward_kernel, (unsigned)blocks, kCellBlock, stream,
+                          reinterpret_cast<const uint32_t *>(gates),
+                          reinterpret_cast<const float2 *>(c_prev),
+                          reinterpret_cast<const uint32_t *>(dh),
+                          reinterpret_cast<const float2 *>(dc_next),
+                          reinterpret_cast<uint32_t *>(dgates), reinterpret_cast<float2 *>(dc_prev),
+                          (unsigned)n_pairs, (unsigned)(H / 2), pack);
+}

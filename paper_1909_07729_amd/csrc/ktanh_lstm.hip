@@ -79,8 +79,7 @@ __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, f
 
 template <bool WIDE>
 __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *__restrict__ gates,
-                                                           const float2 *__restrict__ c_in,
-                                                           float2 *__restrict__ c_out,
+                                                           const float2 *c_in, float2 *c_out,  // may be equal
                                                            uint32_t *__restrict__ h_out, unsigned T,
                                                            unsigned n_pairs, unsigned H2,
                                                            bool always_checked, KtLutPack pack)

@@ -31,8 +31,7 @@ __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
 }
 
 template <bool F32, int OP, bool WIDE, int kUnroll>
-__global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict__ vin,
-                                                        uint4 *__restrict__ vout,
+__global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *vin, uint4 *vout,  // may be equal
                                                         unsigned long long nvec, EdgeArgs edge,
                                                         KtLutPack pack)
 {
@@ -77,8 +76,7 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *__restrict_
 
 // Fallback when `in` and `out` disagree modulo 16 bytes: one element per lane and pass.
 template <bool F32, int OP, bool WIDE>
-__global__ __launch_bounds__(kBlock) void element_kernel(const void *__restrict__ in,
-                                                         void *__restrict__ out,
+__global__ __launch_bounds__(kBlock) void element_kernel(const void *in, void *out,  // may be equal
                                                          unsigned long long n, KtLutPack pack)
 {
     const LaneTable tab(pack);

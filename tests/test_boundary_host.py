@@ -169,3 +169,20 @@ def test_sizes_beyond_the_grid_limit_are_rejected_on_the_host(binding):
     assert lib.klstm_cell(fake, fake, fake, fake, 1, 1 << 20, 1 << 9, None, null) == 4
     assert lib.klstm_cell(fake, fake, fake, fake, 1 << 31, 1, 8, None, null) == 4
     assert lib.klstm_cell64(fake, fake, fake, fake, 1, 1 << 20, 1 << 9, None, null) == 4
+
+
+def test_gradient_entry_points_reject_bad_arguments(binding):
+    lib = binding.load_library()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
+        fn = getattr(lib, name)
+        assert fn(null, null, null, 0, null) == 0
+        assert fn(fake, null, fake, 8, null) == 1
+        assert fn(fake, fake, ctypes.c_void_p(0x1001), 8, null) == 2
+        assert fn(fake, fake, fake, (1 << 40) + 8, null) == 4
+    bw = lib.klstm_cell_backward
+    assert bw(null, null, null, null, null, null, 0, 8, None, null) == 0
+    assert bw(fake, fake, fake, null, fake, fake, 2, 8, None, null) == 1
+    assert bw(fake, fake, fake, fake, fake, fake, 2, 12, None, null) == 4
+    assert bw(fake, fake, ctypes.c_void_p(0x1008), fake, fake, fake, 2, 8, None, null) == 2
+    assert bw(fake, fake, fake, fake, fake, fake, 1 << 20, 1 << 9, None, null) == 4

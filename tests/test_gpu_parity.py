@@ -492,3 +492,51 @@ def test_derived_ops_and_lstm_on_64_interval_tables(gpu, oracle):
         assert np.array_equal(np.isnan(c_got.cpu().numpy()), cn)
         assert np.array_equal(c_got.cpu().numpy().view(np.uint32)[~cn], c_ref.view(np.uint32)[~cn])
         _assert_bf16_equal(_to_host(h_got, np.uint16).ravel(), h_ref.ravel(), False, "klstm_cell64 h")
+
+
+# ------------------------------------------------------------------ gradients
+def test_backward_of_ktanh_and_ksigmoid(gpu, oracle):
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(51))
+    base = wl.all_bf16_patterns()
+    fwd = np.concatenate([base, base, wl.mlp_preactivations(100003, seed=52)])
+    dy = np.concatenate([rng.permutation(base), wl.f32_to_bf16_bits(rng.standard_normal(base.size + 100003, dtype=np.float32))])
+    for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
+        with np.errstate(all="ignore"):
+            want = getattr(oracle, name.replace("_bf16", ""))(dy, fwd)
+        got = _to_host(getattr(binding, name)(_to_dev(torch, dy), _to_dev(torch, fwd)), np.uint16)
+        _assert_bf16_equal(got, want, False, name)
+        # ragged length, unaligned views (element-wise kernel), result written over dy
+        n = 8192 + 13
+        dyd, fd = _to_dev(torch, dy), _to_dev(torch, fwd)
+        for off in (0, 1, 5):
+            outd = torch.full((n + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+            getattr(binding, name)(dyd[off:off + n], fd[off:off + n], dx=outd[8:8 + n])
+            res = _to_host(outd, np.uint16)
+            _assert_bf16_equal(res[8:8 + n], want[off:off + n], False, f"{name} offset {off}")
+            assert np.all(res[:8] == 0x5A5A) and np.all(res[8 + n:] == 0x5A5A)
+        getattr(binding, name)(dyd, fd, dx=dyd)
+        _assert_bf16_equal(_to_host(dyd, np.uint16), want, False, name + " in place")
+
+
+@pytest.mark.parametrize("B,H", [(1, 8), (5, 24), (3, 2056), (256, 2048)])
+def test_lstm_cell_backward(gpu, oracle, B, H):
+    binding, torch = gpu
+    g3, c0 = wl.lstm_cell_inputs(1, B, H)
+    gates = g3[0]
+    rng = np.random.Generator(np.random.PCG64(53))
+    dh = wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32))
+    dcn = rng.standard_normal((B, H), dtype=np.float32)
+    if B * H >= 64:
+        edge = wl.edge_bf16_patterns()
+        gates.reshape(-1)[: edge.size] = edge                 # zeros, thresholds, Inf, NaN in the i-gate
+        c0.reshape(-1)[:4] = [np.inf, -np.inf, np.nan, 1e-40]
+    with np.errstate(all="ignore"):
+        dg_ref, dc_ref = oracle.klstm_cell_backward(gates, c0, dh, dcn)
+    dg, dc = binding.klstm_cell_backward(_to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0"), _to_dev(torch, dh),
+                                         torch.from_numpy(dcn).to("cuda:0"))
+    _assert_bf16_equal(_to_host(dg, np.uint16).ravel(), dg_ref.ravel(), False, "dgates")
+    dc = dc.cpu().numpy()
+    nanp = np.isnan(dc_ref)
+    assert np.array_equal(np.isnan(dc), nanp)
+    assert np.array_equal(dc.view(np.uint32)[~nanp], dc_ref.view(np.uint32)[~nanp])
