@@ -9,8 +9,9 @@
  *   - `lut` is a HOST pointer to the 96-byte parameter table; it is read during the call and
  *     travels to the GPU inside the kernel arguments.  NULL selects the paper's Table 1.
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls only enqueue
- *     work: they return without synchronising, keep no global state and may be issued from
- *     several host threads.
+ *     work: they return without synchronising and may be issued from several host threads.  The
+ *     library keeps nothing between calls except two values computed once per process (the
+ *     device's compute-unit count and the fitted 64-interval table).
  *   - BFloat16 tensors are arrays of uint16_t bit patterns (s:1, E:8, M:7); Float32 tensors of
  *     K-TanH are arrays of uint32_t bit patterns (s:1, E:8, M:23).  Tensors are dense and 1-D as
  *     far as the library is concerned (any contiguous shape works).
