@@ -254,6 +254,9 @@ def run_probe(torch, binding, wl, upload, headline, x):
         headline(i)
     for i in range(ROTATE):
         binding.ktanh64_bf16(headline.inputs[i], out=headline.outputs[i])
+    for i in range(ROTATE):
+        binding.ktanh_bf16_backward(headline.inputs[i], headline.outputs[(i + 1) % ROTATE],
+                                    dx=headline.outputs[i])
     spare = [torch.empty_like(x) for _ in range(4)]
     for k in range(4):
         spare[k].copy_(headline.inputs[k + 4])      # plain copy: 52,428,800 B read + as many written
@@ -292,6 +295,9 @@ def run_probe(torch, binding, wl, upload, headline, x):
         binding.klstm_cell(gates, c0)
     for t in range(8):
         binding.klstm_cell(gates[t:t + 1], c0)
+    dh = torch.zeros((c0.shape[0], c0.shape[1]), dtype=gates.dtype, device=gates.device)
+    for t in range(8):
+        binding.klstm_cell_backward(gates[t], c0, dh, c0)
     torch.cuda.synchronize()
     print("probe done")
 
