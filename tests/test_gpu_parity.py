@@ -195,7 +195,11 @@ def _lstm_check(gpu, oracle, gates, c0, per_step):
     _assert_bf16_equal(h_got.ravel(), h_ref.ravel(), False, "h_out")
 
 
-@pytest.mark.parametrize("T,B,H", [(1, 1, 8), (3, 5, 24), (4, 7, 2048 + 8), (2, 300, 64)])
+# T below, at and above the depth of the gate prefetch ring and twice that depth (the kernel switches
+# from its start-up path to the steady loop there), with lane counts that leave ragged last blocks.
+@pytest.mark.parametrize("T,B,H", [(1, 1, 8), (3, 5, 24), (4, 7, 2048 + 8), (2, 300, 64), (5, 3, 40),
+                                   (7, 2, 264), (8, 3, 72), (9, 5, 24), (11, 2, 520), (12, 1, 8),
+                                   (13, 3, 136), (16, 2, 72), (23, 2, 200)])
 def test_lstm_cell_small(gpu, oracle, T, B, H):
     gates, c0 = wl.lstm_cell_inputs(T, B, H)
     _lstm_check(gpu, oracle, gates, c0, per_step=False)
@@ -209,6 +213,20 @@ def test_lstm_cell_special_values(gpu, oracle):
     gates.reshape(-1)[: edge.size] = edge
     c0.reshape(-1)[:6] = [np.inf, -np.inf, np.nan, 0.0, -0.0, 1e-40]
     _lstm_check(gpu, oracle, gates, c0, per_step=False)
+
+
+def test_lstm_cell_special_values_late_in_a_long_sequence(gpu, oracle):
+    """NaN and infinite gates first appear at steps inside the steady loop and inside the last steps;
+    every earlier step must be unaffected and every later one must carry the poisoned state."""
+    T, B, H = 19, 3, 72
+    gates, c0 = wl.lstm_cell_inputs(T, B, H)
+    edge = wl.edge_bf16_patterns()
+    for t, b in ((2, 0), (6, 1), (9, 2), (13, 0), (17, 1), (18, 2)):
+        row = gates[t, b]
+        row[(7 * t) % 40: (7 * t) % 40 + edge.size] = edge[: row.size - (7 * t) % 40]
+    c0.reshape(-1)[:4] = [np.inf, -np.inf, np.nan, 3.0e38]
+    _lstm_check(gpu, oracle, gates, c0, per_step=False)
+    _lstm_check(gpu, oracle, gates, c0, per_step=True)
 
 
 def test_lstm_cell_full(gpu, oracle):
