@@ -558,3 +558,45 @@ def test_lstm_cell_backward(gpu, oracle, B, H):
     nanp = np.isnan(dc_ref)
     assert np.array_equal(np.isnan(dc), nanp)
     assert np.array_equal(dc.view(np.uint32)[~nanp], dc_ref.view(np.uint32)[~nanp])
+
+
+def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
+    """torch.autograd through ktanh, ksigmoid and two LSTM-cell steps: the gradients that reach the
+    leaves must be the oracle's, chained by hand in the same order."""
+    binding, torch = gpu
+    from paper_1909_07729_amd import autograd as kt
+    rng = np.random.Generator(np.random.PCG64(57))
+
+    def bf16_leaf(bits):
+        return _to_dev(torch, bits).view(torch.bfloat16).requires_grad_()
+
+    x = wl.mlp_preactivations(50021, seed=58)
+    dy = wl.f32_to_bf16_bits(rng.standard_normal(x.size, dtype=np.float32))
+    for fn, fwd, bwd in ((kt.ktanh, oracle.ktanh_bf16, oracle.ktanh_backward),
+                         (kt.ksigmoid, oracle.ksigmoid, oracle.ksigmoid_backward)):
+        xd = bf16_leaf(x)
+        yd = fn(xd)
+        yd.backward(_to_dev(torch, dy).view(torch.bfloat16))
+        y_ref = fwd(x, None)
+        _assert_bf16_equal(_to_host(yd.detach().view(torch.int16), np.uint16), y_ref, False, fn.__name__)
+        _assert_bf16_equal(_to_host(xd.grad.view(torch.int16), np.uint16), bwd(dy, y_ref), False,
+                           fn.__name__ + " grad")
+
+    # two cell steps; the loss sees h of both steps and the final state
+    B, H = 5, 24
+    gates, c0 = wl.lstm_cell_inputs(2, B, H)
+    dh = [wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32)) for _ in range(2)]
+    dc2 = rng.standard_normal((B, H), dtype=np.float32)
+    g = [bf16_leaf(gates[t]) for t in range(2)]
+    c0d = torch.from_numpy(c0).to("cuda:0").requires_grad_()
+    h1, c1 = kt.klstm_cell(g[0], c0d)
+    h2, c2 = kt.klstm_cell(g[1], c1)
+    torch.autograd.backward([h1, h2, c2], [_to_dev(torch, dh[0]).view(torch.bfloat16),
+                                           _to_dev(torch, dh[1]).view(torch.bfloat16),
+                                           torch.from_numpy(dc2).to("cuda:0")])
+    c1_ref, _ = oracle.klstm_cell(gates[:1], c0)
+    dg2_ref, dc1_ref = oracle.klstm_cell_backward(gates[1], c1_ref, dh[1], dc2)
+    dg1_ref, dc0_ref = oracle.klstm_cell_backward(gates[0], c0, dh[0], dc1_ref)
+    _assert_bf16_equal(_to_host(g[1].grad.view(torch.int16), np.uint16).ravel(), dg2_ref.ravel(), False, "dgates step 2")
+    _assert_bf16_equal(_to_host(g[0].grad.view(torch.int16), np.uint16).ravel(), dg1_ref.ravel(), False, "dgates step 1")
+    assert np.array_equal(c0d.grad.cpu().numpy().view(np.uint32), dc0_ref.view(np.uint32))
