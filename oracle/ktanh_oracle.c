@@ -29,7 +29,8 @@
  *                          prints nothing for these: pinned through the
  *                          BFloat16 operations where the two must coincide,
  *                          and by double-precision re-evaluation)
- *   oracle_ktanh_backward, oracle_ksigmoid_backward, oracle_klstm_cell_backward
+ *   oracle_ktanh_backward, oracle_ksigmoid_backward, oracle_klstm_cell_backward,
+ *   oracle_kswish_backward, oracle_kgelu_backward
  *                          gradients for training through K-TanH (Section 3
  *                          trains GNMT with it; the paper does not say how
  *                          the gradient is formed): the derivative identities
@@ -516,6 +517,57 @@ void oracle_ksigmoid_backward(const uint16_t *dy, const uint16_t *sg, uint16_t *
         float sv = widen(sg[i]);
         float one_minus = 1.0f - sv;
         float slope = sv * one_minus;
+        float g = widen(dy[i]) * slope;
+        dx[i] = narrow_rne(g);
+    }
+}
+
+/* dx = dy * Swish'(x), Swish'(x) = s + x*(s*(1 - s)), with s = Sigmoid(x)
+ * recomputed from x through K-TanH exactly as oracle_kswish forms it. */
+void oracle_kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                            const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float xv = widen(x[i]);
+        float sg = ksigmoid_f32_of_bf16(x[i], lut);
+        float one_minus = 1.0f - sg;
+        float bell = sg * one_minus;
+        float xbell = xv * bell;
+        float slope = sg + xbell;
+        float g = widen(dy[i]) * slope;
+        dx[i] = narrow_rne(g);
+    }
+}
+
+/* dx = dy * GELU'(x) for the tanh form: with u = c*(x + a*x^3) and t = TanH(u)
+ * (K-TanH on the BFloat16 value of u, as oracle_kgelu forms it),
+ *   GELU'(x) = 0.5*(1 + t) + (0.5*x) * ((1 - t*t) * (c*(1 + 3a*x^2))),
+ * 3a written as the Float32 constant 0.134145. */
+void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                           const oracle_lut *lut)
+{
+    const float a = 0.044715f;
+    const float a3 = 0.134145f;
+    const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
+    for (size_t i = 0; i < n; ++i) {
+        float xv = widen(x[i]);
+        float x2 = xv * xv;
+        float x3 = x2 * xv;
+        float ax3 = a * x3;
+        float inner = xv + ax3;
+        float arg = c * inner;
+        float th = widen(ktanh_bf16_scalar(narrow_rne(arg), lut));
+        float one_plus = 1.0f + th;
+        float left = 0.5f * one_plus;
+        float th2 = th * th;
+        float sech2 = 1.0f - th2;
+        float a3x2 = a3 * x2;
+        float poly = 1.0f + a3x2;
+        float du = c * poly;
+        float chain = sech2 * du;
+        float half_x = 0.5f * xv;
+        float right = half_x * chain;
+        float slope = left + right;
         float g = widen(dy[i]) * slope;
         dx[i] = narrow_rne(g);
     }

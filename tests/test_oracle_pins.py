@@ -571,3 +571,55 @@ def test_lstm_cell_backward(oracle):
     edc = dcn + dhv * eo * (1 - etc ** 2)
     exact = np.stack([edc * eg * ei * (1 - ei), edc * c0 * ef * (1 - ef), edc * ei * (1 - eg ** 2), dhv * etc * eo * (1 - eo)], axis=1)
     assert np.max(np.abs(got - exact)) <= 0.15 and np.mean(np.abs(got - exact)) <= 0.01
+
+
+def test_backward_of_kswish_and_kgelu(oracle):
+    """Gradients from the forward INPUT: hand-worked values, the exact derivatives as closed forms
+    (distance bounded, so a dropped or mis-signed term shows), slope(x) + slope(-x) = 1, which holds
+    for both functions because K-TanH is odd, and float64 re-evaluation around the pinned K-TanH."""
+    for op, dy, xin, dx, *_ in read_golden("gradient_spot_values.txt"):
+        got = getattr(oracle, op)(np.array([int(dy, 16)], np.uint16), np.array([int(xin, 16)], np.uint16))[0]
+        assert int(got) == int(dx, 16), f"{op} dy={dy} x={xin}: got {int(got):04X}, expected {dx}"
+
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    act = np.abs(xv) <= 16
+    ones = np.full(x.size, 0x3F80, dtype=np.uint16)
+    sw = _bf16_val(oracle.kswish_backward(ones, x))
+    ge = _bf16_val(oracle.kgelu_backward(ones, x))
+    s_true = 1.0 / (1.0 + np.exp(-xv.clip(-80, 80)))
+    sw_true = s_true * (1.0 + xv * (1.0 - s_true))
+    u = np.sqrt(2.0 / np.pi) * (xv + 0.044715 * xv ** 3)
+    t_true = np.tanh(u)
+    ge_true = 0.5 * (1.0 + t_true) + 0.5 * xv * (1.0 - t_true ** 2) * np.sqrt(2.0 / np.pi) * (1.0 + 3 * 0.044715 * xv ** 2)
+    assert np.max(np.abs(sw - sw_true)[act]) <= 0.015 and np.mean(np.abs(sw - sw_true)[act]) <= 3e-4
+    assert np.max(np.abs(ge - ge_true)[act]) <= 0.023 and np.mean(np.abs(ge - ge_true)[act]) <= 3e-4
+    # odd K-TanH: the two slopes at x and -x add up to 1, up to the rounding of each
+    sw_neg = _bf16_val(oracle.kswish_backward(ones, x ^ 0x8000))
+    ge_neg = _bf16_val(oracle.kgelu_backward(ones, x ^ 0x8000))
+    assert np.max(np.abs(sw + sw_neg - 1.0)[act]) <= 2.0 ** -7
+    assert np.max(np.abs(ge + ge_neg - 1.0)[act]) <= 2.0 ** -7
+
+    # float64 re-evaluation with random upstream gradients
+    rng = np.random.Generator(np.random.PCG64(35))
+    dy = wl.f32_to_bf16_bits(rng.standard_normal(x.size, dtype=np.float32))
+    dv = _bf16_val(dy)
+    k = _bf16_val(oracle.ktanh_bf16(_round_f64_to_bf16(xv / 2)))
+    s = (1.0 + k) / 2.0
+    with np.errstate(over="ignore", invalid="ignore"):
+        want = dv * (s + xv * (s * (1.0 - s)))
+    ok = np.isfinite(want) & (np.abs(want) < 3.0e38)
+    assert ok.mean() > 0.99
+    assert np.max(_ulp_distance_bf16(oracle.kswish_backward(dy, x)[ok], _round_f64_to_bf16(want[ok]))) <= 1
+
+    xf = xv.astype(np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        arg32 = np.float32(0.7978845608028654) * (xf + np.float32(0.044715) * ((xf * xf) * xf))
+        t = _bf16_val(oracle.ktanh_bf16(wl.f32_to_bf16_bits(arg32)))
+        want = dv * (0.5 * (1.0 + t) + 0.5 * xv * ((1.0 - t * t) * (np.sqrt(2.0 / np.pi) * (1.0 + 0.134145 * xv * xv))))
+    ok = np.isfinite(want) & (np.abs(want) < 3.0e38) & (np.abs(xv) < 1e18)
+    assert ok.mean() > 0.7        # |x| up to 1e18: beyond 1.8e19 x*x overflows Float32 and 0 * inf = NaN
+    got = oracle.kgelu_backward(dy, x)
+    # where the slope nearly cancels (left + right close to 0) the float32 sum keeps fewer bits
+    loose = np.abs(_bf16_val(got[ok]) - want[ok]) <= 2.0 ** -8 * np.abs(want[ok]) + 1e-6 * np.abs(dv[ok]) * (1 + np.abs(xv[ok]) ** 3)
+    assert np.all(loose)
