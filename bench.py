@@ -183,6 +183,11 @@ def run_extras(torch, binding, wl, upload, xs, ys):
            lambda i: binding.ktanh_bf16_backward(xs[i % ROTATE], ys[(i + 1) % ROTATE], dx=ys[i % ROTATE]),
            xs[0].numel(), 6, 2000, 500)
 
+    for name in ("kswish_backward", "kgelu_backward"):
+        record(name, "dy, x and dx as the headline tensor (6 B per element), 8 rotating triples; the K-TanH value is rebuilt from x",
+               lambda i, fn=getattr(binding, name): fn(xs[(i + 1) % ROTATE], xs[i % ROTATE], dx=ys[i % ROTATE]),
+               xs[0].numel(), 6, 2000, 500)
+
     # the large tensors rotate as well: a 537 MB working set still keeps part of itself in the cache
     x4 = [upload(wl.mlp_preactivations())]
     for k in range(1, 4):
@@ -257,6 +262,8 @@ def run_probe(torch, binding, wl, upload, headline, x):
     for i in range(ROTATE):
         binding.ktanh_bf16_backward(headline.inputs[i], headline.outputs[(i + 1) % ROTATE],
                                     dx=headline.outputs[i])
+    for i in range(ROTATE):
+        binding.kgelu_backward(headline.inputs[(i + 1) % ROTATE], headline.inputs[i], dx=headline.outputs[i])
     spare = [torch.empty_like(x) for _ in range(4)]
     for k in range(4):
         spare[k].copy_(headline.inputs[k + 4])      # plain copy: 52,428,800 B read + as many written

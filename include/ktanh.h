@@ -195,6 +195,20 @@ ktanh_status_t ktanh_bf16_backward(const uint16_t *dy, const uint16_t *y, uint16
 ktanh_status_t ksigmoid_backward(const uint16_t *dy, const uint16_t *s, uint16_t *dx, size_t n,
                                  ktanh_stream_t stream);
 
+/* Gradients of the Swish and GELU identities of Section 1 with the K-TanH value in place of TanH,
+ * from the forward INPUT x (the value is rebuilt exactly as kswish / kgelu form it):
+ *   kswish_backward:  dx = bf16( dy * (s + x*(s*(1 - s))) ),                      s = Sigmoid(x)
+ *   kgelu_backward:   dx = bf16( dy * (0.5*(1 + t) + (0.5*x)*((1 - t*t)*(c*(1 + a3*(x*x))))) ),
+ *                     t = K(bf16(c*(x + a*x^3))), a = 0.044715, a3 = 0.134145 (= 3a), c = sqrt(2/pi)
+ * BFloat16 tensors of n elements, device; `lut` as for the forward calls (host pointer, NULL =
+ * Table 1).  Float32 arithmetic, one rounding per operation in the order written, result rounded
+ * to nearest even.  Non-finite intermediates behave as the operations give (x*x overflows beyond
+ * |x| = 1.8e19 and the GELU slope is then NaN).  dx may alias dy or x. */
+ktanh_status_t kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                               const ktanh_lut_t *lut, ktanh_stream_t stream);
+ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                              const ktanh_lut_t *lut, ktanh_stream_t stream);
+
 /* One klstm_cell step backwards.  The forward activations are recomputed from the gate
  * pre-activations with K-TanH exactly as klstm_cell forms them (i, f, o, g, c' = f*c + i*g,
  * tc = K(bf16(c'))); then, in Float32, one rounding per operation:

@@ -6,7 +6,8 @@ Plumbing only: each ``forward`` is one call of a forward entry point, each ``bac
 the matching gradient entry point; all arithmetic runs in the library's kernels.  Tensors are
 ``torch.bfloat16`` (Float32 for the LSTM cell state), on the GPU.  The gradient is the derivative
 identity of the exact function evaluated on the K-TanH output (``dy * (1 - y^2)``,
-``dy * s * (1 - s)``); the tables get no gradient.
+``dy * s * (1 - s)``, and the derivatives of the Swish and GELU identities); the tables get no
+gradient.
 """
 from __future__ import annotations
 
@@ -41,6 +42,34 @@ class _KSigmoid(torch.autograd.Function):
         return binding.ksigmoid_backward(dy.contiguous(), s), None
 
 
+class _KSwish(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, lut):
+        x = x.contiguous()
+        ctx.save_for_backward(x)
+        ctx.lut = lut
+        return binding.kswish(x, lut=lut)
+
+    @staticmethod
+    def backward(ctx, dy):
+        (x,) = ctx.saved_tensors
+        return binding.kswish_backward(dy.contiguous(), x, lut=ctx.lut), None
+
+
+class _KGelu(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, lut):
+        x = x.contiguous()
+        ctx.save_for_backward(x)
+        ctx.lut = lut
+        return binding.kgelu(x, lut=lut)
+
+    @staticmethod
+    def backward(ctx, dy):
+        (x,) = ctx.saved_tensors
+        return binding.kgelu_backward(dy.contiguous(), x, lut=ctx.lut), None
+
+
 class _KLstmCell(torch.autograd.Function):
     @staticmethod
     def forward(ctx, gates, c_prev, lut):
@@ -71,6 +100,16 @@ def ktanh(x: torch.Tensor, lut=None) -> torch.Tensor:
 def ksigmoid(x: torch.Tensor, lut=None) -> torch.Tensor:
     """Sigmoid through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
     return _KSigmoid.apply(x, lut)
+
+
+def kswish(x: torch.Tensor, lut=None) -> torch.Tensor:
+    """Swish through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
+    return _KSwish.apply(x, lut)
+
+
+def kgelu(x: torch.Tensor, lut=None) -> torch.Tensor:
+    """GELU (tanh form) through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
+    return _KGelu.apply(x, lut)
 
 
 def klstm_cell(gates: torch.Tensor, c_prev: torch.Tensor, lut=None):

@@ -21,7 +21,8 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32",
            "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
            "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
-           "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward")
+           "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
+           "kswish_backward", "kgelu_backward")
 
 
 class KtanhLut(ctypes.Structure):
@@ -114,6 +115,10 @@ def load_library() -> ctypes.CDLL:
         for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, sz, vp]
+            fn.restype = ctypes.c_int
+        for name in ("kswish_backward", "kgelu_backward"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, vp, sz, lp, vp]
             fn.restype = ctypes.c_int
         lib.klstm_cell_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz, lp, vp]
         lib.klstm_cell_backward.restype = ctypes.c_int
@@ -324,6 +329,31 @@ def ktanh_bf16_backward(dy, y, dx=None, stream=None):
 def ksigmoid_backward(dy, s, dx=None, stream=None):
     """dx = dy * s * (1 - s) from the forward Sigmoid output s (BFloat16 tensors)."""
     return _backward("ksigmoid_backward", dy, s, dx, stream)
+
+
+def _backward_from_input(name, dy, x, dx, lut, stream):
+    _check(dy, _BF16_VIEWS, "dy")
+    _check(x, _BF16_VIEWS, "x")
+    if dx is None:
+        dx = torch.empty_like(dy)
+    _check(dx, _BF16_VIEWS, "dx")
+    if not (dy.numel() == x.numel() == dx.numel()):
+        raise ValueError("dy, x and dx differ in size")
+    st = getattr(load_library(), name)(dy.data_ptr(), x.data_ptr(), dx.data_ptr(), dy.numel(),
+                                       _lut_arg(lut), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, name)
+    return dx
+
+
+def kswish_backward(dy, x, dx=None, lut=None, stream=None):
+    """dx = dy * (s + x*s*(1 - s)), s = Sigmoid(x) through K-TanH, from the forward input x."""
+    return _backward_from_input("kswish_backward", dy, x, dx, lut, stream)
+
+
+def kgelu_backward(dy, x, dx=None, lut=None, stream=None):
+    """dx = dy * GELU'(x) of the tanh form with K-TanH inside, from the forward input x."""
+    return _backward_from_input("kgelu_backward", dy, x, dx, lut, stream)
 
 
 def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None):

@@ -1,5 +1,6 @@
 // libktanh: gradients for training through K-TanH -- the derivative identities of TanH and Sigmoid
-// on the forward outputs, and one LSTM-cell step backwards -- and their entry points.
+// on the forward outputs, the derivatives of the Swish and GELU identities from the forward inputs,
+// and one LSTM-cell step backwards -- and their entry points.
 #include "ktanh_device.h"
 
 using namespace ktanh_device;
@@ -85,6 +86,137 @@ ktanh_status_t launch_grad(const uint16_t *dy, const uint16_t *fwd, uint16_t *dx
     const size_t want = (n + kBlock - 1) / kBlock;
     return launch_checked(grad_element_kernel<GRAD>, (unsigned)(want < 8192 ? want : 8192), kBlock,
                           stream, dy, fwd, dx, (unsigned long long)n);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Swish and GELU: the slope needs the K-TanH value, which is rebuilt from the forward input x with
+// the device functions the forward kernels use.
+//   Swish' = s + x * (s * (1 - s)),                 s = Sigmoid(x)
+//   GELU'  = 0.5 * (1 + t) + (0.5 * x) * ((1 - t^2) * (c * (1 + 3a * x^2))),   t = K(c * (x + a x^3))
+// Float32, one rounding per written operation.
+enum GradFromInput { GRAD_SWISH = 0, GRAD_GELU = 1 };
+
+template <int GRAD>
+__device__ __forceinline__ uint32_t grad_from_input_pair(uint32_t dy2, uint32_t x2,
+                                                         const LaneTable &tab)
+{
+    const float dy[2] = {widen_lo(dy2), widen_hi(dy2)};
+    const float x[2] = {widen_lo(x2), widen_hi(x2)};
+    float slope[2];
+    if constexpr (GRAD == GRAD_SWISH) {
+        float s[2];
+        ksigmoid_f32_pair<true, false>(x2, tab, s[0], s[1]);
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const float one_minus = 1.0f - s[k];
+            const float bell = s[k] * one_minus;
+            const float xbell = x[k] * bell;
+            slope[k] = s[k] + xbell;
+        }
+    } else {
+        const float a = 0.044715f;
+        const float a3 = 0.134145f;
+        const float c = 0.7978845608028654f;
+        float sq[2], u[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            sq[k] = x[k] * x[k];
+            const float cube = sq[k] * x[k];
+            const float acube = a * cube;
+            const float inner = x[k] + acube;
+            u[k] = c * inner;
+        }
+        const uint32_t t2 = ktanh_pair<true, false>(narrow_pair(u[0], u[1]), tab);
+        const float t[2] = {widen_lo(t2), widen_hi(t2)};
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const float one_plus = 1.0f + t[k];
+            const float left = 0.5f * one_plus;
+            const float tsq = t[k] * t[k];
+            const float sech2 = 1.0f - tsq;
+            const float a3sq = a3 * sq[k];
+            const float poly = 1.0f + a3sq;
+            const float du = c * poly;
+            const float chain = sech2 * du;
+            const float half_x = 0.5f * x[k];
+            const float right = half_x * chain;
+            slope[k] = left + right;
+        }
+    }
+    return narrow_pair(dy[0] * slope[0], dy[1] * slope[1]);
+}
+
+// Same shape as grad_stream_kernel.  The table reads need every lane enabled, so the bounds
+// predicate only the loads and stores; the loose elements are taken by the whole last block.
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_input_stream_kernel(
+    const uint4 *vdy, const uint4 *vx, uint4 *vdx, unsigned long long nvec, const uint16_t *dy,
+    const uint16_t *x, uint16_t *dx, unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const bool live = at < nvec;
+    uint4 a = uint4{0u, 0u, 0u, 0u}, b = uint4{0u, 0u, 0u, 0u};
+    if (live) {
+        a = load_stream(vdy + at);
+        b = load_stream(vx + at);
+    }
+    const uint4 r = uint4{grad_from_input_pair<GRAD>(a.x, b.x, tab), grad_from_input_pair<GRAD>(a.y, b.y, tab),
+                          grad_from_input_pair<GRAD>(a.z, b.z, tab), grad_from_input_pair<GRAD>(a.w, b.w, tab)};
+    if (live) store_stream(vdx + at, r);
+    if (blockIdx.x == gridDim.x - 1) {  // uniform over the block
+        const unsigned long long loose = nvec * 8 + threadIdx.x;
+        const bool some = loose < n;
+        const uint32_t d1 = some ? dy[loose] : 0u, x1 = some ? x[loose] : 0u;
+        const uint32_t r1 = grad_from_input_pair<GRAD>(d1, x1, tab);
+        if (some) dx[loose] = (uint16_t)r1;
+    }
+}
+
+// Any alignment: one element per lane and pass; the trip count is the same for the whole block.
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_input_element_kernel(const uint16_t *dy,
+                                                                    const uint16_t *x, uint16_t *dx,
+                                                                    unsigned long long n,
+                                                                    KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n; base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool some = i < n;
+        const uint32_t d1 = some ? dy[i] : 0u, x1 = some ? x[i] : 0u;
+        const uint32_t r1 = grad_from_input_pair<GRAD>(d1, x1, tab);
+        if (some) dx[i] = (uint16_t)r1;
+    }
+}
+
+template <int GRAD>
+ktanh_status_t launch_grad_from_input(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                                      const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (n == 0) return KT_OK;
+    if (dy == nullptr || x == nullptr || dx == nullptr) return KT_ERR_NULL;
+    const uintptr_t all = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(x) |
+                          reinterpret_cast<uintptr_t>(dx);
+    if (all & 1) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
+    KtLutPack pack;
+    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    if (st != KT_OK) return st;
+    if ((all & 15) == 0) {
+        const size_t nvec = n / 8;
+        size_t tiles = (nvec + kBlock - 1) / kBlock;
+        if (tiles == 0) tiles = 1;
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+        return launch_checked(grad_input_stream_kernel<GRAD>, (unsigned)tiles, kBlock, stream,
+                              reinterpret_cast<const uint4 *>(dy), reinterpret_cast<const uint4 *>(x),
+                              reinterpret_cast<uint4 *>(dx), (unsigned long long)nvec, dy, x, dx,
+                              (unsigned long long)n, pack);
+    }
+    const size_t want = (n + kBlock - 1) / kBlock;
+    return launch_checked(grad_input_element_kernel<GRAD>, (unsigned)(want < 8192 ? want : 8192),
+                          kBlock, stream, dy, x, dx, (unsigned long long)n, pack);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -176,6 +308,18 @@ extern "C" ktanh_status_t ksigmoid_backward(const uint16_t *dy, const uint16_t *
                                             size_t n, ktanh_stream_t stream)
 {
     return launch_grad<GRAD_SIGMOID>(dy, s, dx, n, stream);
+}
+
+extern "C" ktanh_status_t kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
+                                          size_t n, const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad_from_input<GRAD_SWISH>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
+                                         size_t n, const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad_from_input<GRAD_GELU>(dy, x, dx, n, lut, stream);
 }
 
 extern "C" ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev,

@@ -180,6 +180,15 @@ def test_gradient_entry_points_reject_bad_arguments(binding):
         assert fn(fake, null, fake, 8, null) == 1
         assert fn(fake, fake, ctypes.c_void_p(0x1001), 8, null) == 2
         assert fn(fake, fake, fake, (1 << 40) + 8, null) == 4
+    bad = binding.ktanh_default_lut()
+    bad.r[5] = 9
+    for name in ("kswish_backward", "kgelu_backward"):
+        fn = getattr(lib, name)
+        assert fn(null, null, null, 0, None, null) == 0
+        assert fn(fake, fake, null, 8, None, null) == 1
+        assert fn(ctypes.c_void_p(0x1001), fake, fake, 8, None, null) == 2
+        assert fn(fake, fake, fake, (1 << 40) + 8, None, null) == 4
+        assert fn(fake, fake, fake, 8, ctypes.byref(bad), null) == 3
     bw = lib.klstm_cell_backward
     assert bw(null, null, null, null, null, null, 0, 8, None, null) == 0
     assert bw(fake, fake, fake, null, fake, fake, 2, 8, None, null) == 1

@@ -537,6 +537,41 @@ def test_backward_of_ktanh_and_ksigmoid(gpu, oracle):
         _assert_bf16_equal(_to_host(dyd, np.uint16), want, False, name + " in place")
 
 
+def test_backward_of_kswish_and_kgelu(gpu, oracle):
+    """Gradients from the forward input: every BFloat16 pattern as x (twice, against shuffled and
+    random upstream gradients), ragged and unaligned views, in place over dy and over x, and a
+    caller's table."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(59))
+    base = wl.all_bf16_patterns()
+    x = np.concatenate([base, base, wl.mlp_preactivations(100003, seed=60)])
+    dy = np.concatenate([rng.permutation(base), wl.f32_to_bf16_bits(rng.standard_normal(base.size + 100003, dtype=np.float32))])
+    rows = _random_valid_table(np.random.Generator(np.random.PCG64(61)), 32)
+    for name in ("kswish_backward", "kgelu_backward"):
+        with np.errstate(all="ignore"):
+            want = getattr(oracle, name)(dy, x)
+            want_custom = getattr(oracle, name)(dy, x, oracle.OracleLut.from_tuples(rows))
+        dyd, xd = _to_dev(torch, dy), _to_dev(torch, x)
+        _assert_bf16_equal(_to_host(getattr(binding, name)(dyd, xd), np.uint16), want, False, name)
+        got = getattr(binding, name)(dyd, xd, lut=binding.KtanhLut.from_tuples(rows))
+        _assert_bf16_equal(_to_host(got, np.uint16), want_custom, False, name + " custom table")
+        n = 8192 + 13
+        for off in (0, 1, 5):
+            outd = torch.full((n + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+            getattr(binding, name)(dyd[off:off + n], xd[off:off + n], dx=outd[8:8 + n])
+            res = _to_host(outd, np.uint16)
+            _assert_bf16_equal(res[8:8 + n], want[off:off + n], False, f"{name} offset {off}")
+            assert np.all(res[:8] == 0x5A5A) and np.all(res[8 + n:] == 0x5A5A)
+        for n_small in (1, 7, 8, 9, 511, 512, 513):
+            got = getattr(binding, name)(dyd[:n_small].clone(), xd[:n_small].clone())
+            _assert_bf16_equal(_to_host(got, np.uint16), want[:n_small], False, f"{name} n={n_small}")
+        over_dy, over_x = dyd.clone(), xd.clone()
+        getattr(binding, name)(over_dy, xd, dx=over_dy)
+        _assert_bf16_equal(_to_host(over_dy, np.uint16), want, False, name + " over dy")
+        getattr(binding, name)(dyd, over_x, dx=over_x)
+        _assert_bf16_equal(_to_host(over_x, np.uint16), want, False, name + " over x")
+
+
 @pytest.mark.parametrize("B,H", [(1, 8), (5, 24), (3, 2056), (256, 2048)])
 def test_lstm_cell_backward(gpu, oracle, B, H):
     binding, torch = gpu
@@ -572,15 +607,17 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
 
     x = wl.mlp_preactivations(50021, seed=58)
     dy = wl.f32_to_bf16_bits(rng.standard_normal(x.size, dtype=np.float32))
-    for fn, fwd, bwd in ((kt.ktanh, oracle.ktanh_bf16, oracle.ktanh_backward),
-                         (kt.ksigmoid, oracle.ksigmoid, oracle.ksigmoid_backward)):
+    for fn, fwd, bwd, from_input in ((kt.ktanh, oracle.ktanh_bf16, oracle.ktanh_backward, False),
+                                     (kt.ksigmoid, oracle.ksigmoid, oracle.ksigmoid_backward, False),
+                                     (kt.kswish, oracle.kswish, oracle.kswish_backward, True),
+                                     (kt.kgelu, oracle.kgelu, oracle.kgelu_backward, True)):
         xd = bf16_leaf(x)
         yd = fn(xd)
         yd.backward(_to_dev(torch, dy).view(torch.bfloat16))
         y_ref = fwd(x, None)
         _assert_bf16_equal(_to_host(yd.detach().view(torch.int16), np.uint16), y_ref, False, fn.__name__)
-        _assert_bf16_equal(_to_host(xd.grad.view(torch.int16), np.uint16), bwd(dy, y_ref), False,
-                           fn.__name__ + " grad")
+        _assert_bf16_equal(_to_host(xd.grad.view(torch.int16), np.uint16), bwd(dy, x if from_input else y_ref),
+                           False, fn.__name__ + " grad")
 
     # two cell steps; the loss sees h of both steps and the final state
     B, H = 5, 24
