@@ -29,6 +29,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0           # MI355X HBM3E, published peak
 ROTATE = 8                      # distinct buffer pairs the headline steps cycle through
+HEADLINE_ROLL = 4099            # buffer k holds the seeded tensor rotated by k * this many elements
 PAPER_CONTEXT = "paper: 0.28 cycles/TanH, 5.46x over Intel SVML on AVX512 CLX (Table 2) -- other hardware, context only"
 
 
@@ -69,6 +70,29 @@ def time_steps(torch, launch, steps, warmup):
     return wall, start.elapsed_time(stop) * 1e-3
 
 
+def make_upload(np, torch, dev):
+    def upload(a):
+        view = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32}.get(a.dtype, a.dtype)
+        return torch.from_numpy(a.view(view)).to(dev)
+    return upload
+
+
+def make_headline(torch, binding, wl, upload):
+    """The timed step: ktanh_bf16 on the [50,128,4096] gate tensor, over ROTATE buffer pairs (buffer k
+    is the seeded tensor rotated by k * 4099 elements: distinct memory, same value mix).  Returns the
+    step function, with its buffers as attributes, and the host tensor."""
+    x_host = wl.lstm_gate_preactivations()
+    xs = [upload(x_host)]
+    for k in range(1, ROTATE):
+        xs.append(xs[0].roll(k * HEADLINE_ROLL))
+    ys = [torch.empty_like(x) for x in xs]
+
+    def headline(i):
+        binding.ktanh_bf16(xs[i % ROTATE], out=ys[i % ROTATE])
+    headline.inputs, headline.outputs = xs, ys
+    return headline, x_host
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -92,21 +116,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    def upload(a):
-        view = {np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32}.get(a.dtype, a.dtype)
-        return torch.from_numpy(a.view(view)).to(dev)
-
-    # ---- headline workload
-    x_host = wl.lstm_gate_preactivations()
+    upload = make_upload(np, torch, dev)
+    headline, x_host = make_headline(torch, binding, wl, upload)
+    xs, ys = headline.inputs, headline.outputs
     n = x_host.size
-    xs = [upload(x_host)]
-    for k in range(1, ROTATE):
-        xs.append(xs[0].roll(k * 4099))          # distinct buffers, same value mix
-    ys = [torch.empty_like(x) for x in xs]
-
-    def headline(i):
-        binding.ktanh_bf16(xs[i % ROTATE], out=ys[i % ROTATE])
-    headline.inputs, headline.outputs = xs, ys
 
     if args.probe:
         run_probe(torch, binding, wl, upload, headline, xs[0])

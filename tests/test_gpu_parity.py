@@ -152,6 +152,21 @@ def test_rejected_calls_raise(gpu):
 
 
 # ------------------------------------------------------------------ the named workloads, full size
+def test_bench_headline_step_matches_oracle_on_every_buffer(gpu, oracle):
+    """The step bench.py times, built by bench.py itself: same buffers, same call, every one of the
+    rotating outputs against the oracle (element-wise, so the rotated input gives the rotated output)."""
+    binding, torch = gpu
+    import bench
+    headline, x_host = bench.make_headline(torch, binding, wl, bench.make_upload(np, torch, torch.device("cuda:0")))
+    for i in range(2 * bench.ROTATE):
+        headline(i)
+    torch.cuda.synchronize()
+    want = oracle.ktanh_bf16(x_host)
+    for k in range(bench.ROTATE):
+        got = _to_host(headline.outputs[k], np.uint16)
+        assert np.array_equal(got, np.roll(want, k * bench.HEADLINE_ROLL)), f"buffer pair {k}"
+
+
 def test_lstm_gate_preactivations_full(gpu, oracle):
     """[50, 128, 4096] BFloat16 ~ N(0, 1.5^2): the tensor the throughput figure is quoted on."""
     _run_bf16(gpu, oracle, "ktanh_bf16", wl.lstm_gate_preactivations())
