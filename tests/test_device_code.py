@@ -1,0 +1,62 @@
+"""What the compiler made of the kernels, read from the gfx950 assembly of the shipped sources built
+with the shipped flags: no packed Float32 arithmetic, no register spills to scratch memory, and the
+table reads are the cross-lane instruction the design rests on."""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_1909_07729_amd import build
+
+HIP_SOURCES = [s for s in build.SOURCES if s.endswith(".hip")]
+
+
+@pytest.fixture(scope="module")
+def assembly(tmp_path_factory):
+    out = {}
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    tmp = tmp_path_factory.mktemp("asm")
+    procs = []
+    for src in HIP_SOURCES:
+        dst = str(tmp / (src + ".s"))
+        cmd = [hipcc, *flags, "-S", "--cuda-device-only", "-I", os.path.join(build.ROOT, "include"),
+               "-I", build.CSRC, os.path.join(build.CSRC, src), "-o", dst]
+        procs.append((src, dst, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE)))
+    for src, dst, p in procs:
+        _, err = p.communicate(timeout=600)
+        assert p.returncode == 0, err.decode()
+        out[src] = open(dst).read()
+    return out
+
+
+def test_no_packed_float32_arithmetic(assembly):
+    for src, text in assembly.items():
+        hits = re.findall(r"v_pk_(?:add|mul|fma)_f32", text)
+        assert not hits, f"{src}: {len(hits)} packed Float32 instructions"
+
+
+def test_no_kernel_spills_registers(assembly):
+    for src, text in assembly.items():
+        sizes = [int(v) for v in re.findall(r"\.amdhsa_private_segment_fixed_size\s+(\d+)", text)]
+        assert sizes and all(v == 0 for v in sizes), f"{src}: private segment sizes {sizes}"
+        assert "scratch_load" not in text and "scratch_store" not in text, src
+
+
+def test_table_reads_are_cross_lane_and_stores_stream(assembly):
+    for src in ("ktanh_stream.hip", "ktanh_lstm.hip"):
+        text = assembly[src]
+        assert "ds_bpermute_b32" in text, src
+        assert "ds_read" not in text and "ds_write" not in text, f"{src}: the table must not live in LDS"
+        assert re.search(r"global_store_dword(?:x4)? .* sc0 sc1 nt", text), src
+    assert re.search(r"global_load_dwordx4 .* nt", assembly["ktanh_stream.hip"])
+
+
+def test_lstm_steady_loop_waits_for_its_own_gate_words_only(assembly):
+    """With four register stages of four loads each, the step that consumes a stage must wait with
+    twelve to fifteen younger loads still in flight; a wait for everything (vmcnt(0)) inside the
+    steady loop would serialise memory and arithmetic."""
+    text = assembly["ktanh_lstm.hip"]
+    for count in (15, 14, 13, 12):
+        assert f"s_waitcnt vmcnt({count})" in text, count
