@@ -9,6 +9,8 @@
  *
  * What each function follows (arXiv:1909.07729):
  *   oracle_table1          Table 1 (optimised parameters for BFloat16 inputs)
+ *   oracle_fit_lut_bmin0   the ablation of Section 3: the fit with b_min = 0
+ *                          (no table printed; pinned by exhaustive search)
  *   oracle_fit_lut         Section 2.4, Steps 1-3, eq. (1) and the b_min/b_max
  *                          bounds (eq. (2))
  *   oracle_ktanh_bf16/f32  Algorithm 1; thresholds T1, T2 and the interval
@@ -118,7 +120,7 @@ void oracle_table1(oracle_lut *lut)
  *     the mean residual, halves rounded up, then clamped to [b_min, b_max];
  *   - r_max = p = 7; the smallest objective wins, the smaller r on a tie.
  */
-static void fit_intervals(int s, uint8_t *TE, uint8_t *Tr, int8_t *Tb)
+static void fit_intervals(int s, int bmin_zero, uint8_t *TE, uint8_t *Tr, int8_t *Tb)
 {
     const int p = 7, q = 7;
     const int per = 1 << (p - s); /* inputs per interval: 16 for s = 3, 8 for s = 4 */
@@ -173,7 +175,7 @@ static void fit_intervals(int s, uint8_t *TE, uint8_t *Tr, int8_t *Tb)
             long top = ((long)(midx + 1) << (p - s)) - 1; /* largest m in the interval */
             long bmax = (1L << p) - 1 - (top >> r);
             long low_unit = (p - s - r) >= 0 ? (1L << (p - s - r)) : 0; /* floor(2^(p-s-r)) */
-            long bmin = -(long)midx * low_unit;
+            long bmin = bmin_zero ? 0 : -(long)midx * low_unit;
             if (b < bmin) b = bmin;
             if (b > bmax) b = bmax;
             double cost = 0.0;
@@ -189,7 +191,11 @@ static void fit_intervals(int s, uint8_t *TE, uint8_t *Tr, int8_t *Tb)
     }
 }
 
-void oracle_fit_lut(oracle_lut *lut) { fit_intervals(3, lut->E, lut->r, lut->b); }
+void oracle_fit_lut(oracle_lut *lut) { fit_intervals(3, 0, lut->E, lut->r, lut->b); }
+
+/* The sub-optimal tables of the ablation study (Section 3): the same fit with
+ * b_min set to 0, so that the offset can only add. */
+void oracle_fit_lut_bmin0(oracle_lut *lut) { fit_intervals(3, 1, lut->E, lut->r, lut->b); }
 
 /* The 64-interval variant: 4 mantissa MSBs in the index, 8 inputs per interval. */
 typedef struct {
@@ -198,7 +204,7 @@ typedef struct {
     int8_t b[64];
 } oracle_lut64;
 
-void oracle_fit_lut64(oracle_lut64 *lut) { fit_intervals(4, lut->E, lut->r, lut->b); }
+void oracle_fit_lut64(oracle_lut64 *lut) { fit_intervals(4, 0, lut->E, lut->r, lut->b); }
 
 /* ------------------------------------------------------------------ */
 /* Algorithm 1 on one BFloat16 bit pattern (s:1, E:8, M:7).

@@ -40,10 +40,11 @@ def test_fit_regenerates_table1(oracle):
     assert oracle.fit_lut().as_tuples() == _table1_from_text()
 
 
-def _brute_force_fit(s):
+def _brute_force_fit(s, bmin_zero=False):
     """Section 2.4 in numpy, independent of the C fit: Step 2 as written, Step 3 by enumerating
     every (r, b) inside the b_min / b_max bounds and scoring eq. (1).  Returns the table and the
-    smallest ratio runner-up / winner of the Step 3 objective (how far from a tie the fit is)."""
+    smallest ratio runner-up / winner of the Step 3 objective (how far from a tie the fit is).
+    bmin_zero: the ablation's bound b_min = 0."""
     p = 7
     per = 1 << (p - s)
     table, margin = [], np.inf
@@ -65,7 +66,7 @@ def _brute_force_fit(s):
         scored = []
         for r in range(0, p + 1):
             bmax = 2 ** p - 1 - (((j + 1) * 2 ** (p - s) - 1) >> r)
-            bmin = -j * (2 ** (p - s - r) if p - s - r >= 0 else 0)
+            bmin = 0 if bmin_zero else -j * (2 ** (p - s - r) if p - s - r >= 0 else 0)
             for b in range(bmin, bmax + 1):
                 scored.append((np.sum((Mh - (m / 2.0 ** r + b)) ** 2), r, b))
         scored.sort()
@@ -86,6 +87,32 @@ def test_fit64_is_the_brute_force_argmin_of_eq1(oracle):
     table, margin = _brute_force_fit(4)
     assert oracle.fit_lut64().as_tuples() == table
     assert margin > 1.001
+
+
+def test_ablation_fit_with_bmin_zero(oracle):
+    """Section 3's ablation solves the same problem with b_min = 0.  No table is printed for it:
+    the fit is held against the exhaustive search, every offset must be non-negative, intervals
+    whose optimal offset was non-negative anyway must keep their Table 1 entry, and the result must
+    be a worse approximation of TanH than Table 1 (the point of the ablation)."""
+    got = oracle.fit_lut_bmin0().as_tuples()
+    table, margin = _brute_force_fit(3, bmin_zero=True)
+    assert got == table and margin > 1.001
+    ref = _table1_from_text()
+    assert all(b >= 0 for _, _, b in got)
+    changed = [t for t in range(32) if got[t] != ref[t]]
+    assert changed and all(ref[t][2] < 0 for t in changed)
+    assert all(got[t] == ref[t] for t in range(32) if ref[t][2] >= 0)
+    for t, (E, r, b) in enumerate(got):
+        j = t & 7
+        assert 0 <= (j * 16 >> r) + b <= ((j * 16 + 15) >> r) + b <= 127
+    x = wl.all_bf16_patterns()
+    x = x[(x & 0x7FFF) < 0x7F80]
+    xv = _bf16_val(x)
+    err_ref = np.abs(_bf16_val(oracle.ktanh_bf16(x)) - np.tanh(xv))
+    err_abl = np.abs(_bf16_val(oracle.ktanh_bf16(x, oracle.fit_lut_bmin0())) - np.tanh(xv))
+    region = (np.abs(xv) >= 0.25) & (np.abs(xv) < 4.0)
+    assert err_abl[region].mean() > 1.15 * err_ref[region].mean()
+    assert err_abl.max() > 1.5 * err_ref.max()
 
 
 def test_table1_respects_overflow_bounds():
