@@ -115,10 +115,13 @@ typedef struct ktanh_lut64 {
 /* Offline parameter fit of Section 2.4 (Steps 1-3: common output exponent per interval, then the
  * (r, b) that minimise eq. (1) under the overflow bounds b_min, b_max of eq. (2)), for BFloat16
  * inputs.  Host-only, double precision, microseconds; `out` is a host pointer the caller owns.
- * ktanh_fit_lut reproduces Table 1; ktanh_fit_lut64 produces the 64-interval tables.
+ * ktanh_fit_lut reproduces Table 1; ktanh_fit_lut64 produces the 64-interval tables;
+ * ktanh_fit_lut_bmin0 solves the same problem with b_min = 0, the deliberately sub-optimal
+ * parameters of the ablation study in Section 3 (a valid table: pass it as `lut` to see its effect).
  * Returns KT_OK or KT_ERR_NULL. */
 ktanh_status_t ktanh_fit_lut(ktanh_lut_t *out);
 ktanh_status_t ktanh_fit_lut64(ktanh_lut64_t *out);
+ktanh_status_t ktanh_fit_lut_bmin0(ktanh_lut_t *out);
 
 /* Same check as ktanh_lut_validate for a 64-interval table (8 mantissas per interval). */
 ktanh_status_t ktanh_lut64_validate(const ktanh_lut64_t *lut);

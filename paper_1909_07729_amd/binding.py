@@ -22,7 +22,7 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
            "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
            "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
-           "kswish_backward", "kgelu_backward")
+           "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0")
 
 
 class KtanhLut(ctypes.Structure):
@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
         lp64 = ctypes.POINTER(KtanhLut64)
         lib.ktanh_fit_lut.argtypes = [lp]
         lib.ktanh_fit_lut.restype = ctypes.c_int
+        lib.ktanh_fit_lut_bmin0.argtypes = [lp]
+        lib.ktanh_fit_lut_bmin0.restype = ctypes.c_int
         lib.ktanh_fit_lut64.argtypes = [lp64]
         lib.ktanh_fit_lut64.restype = ctypes.c_int
         lib.ktanh_lut64_validate.argtypes = [lp64]
@@ -148,6 +150,15 @@ def ktanh_fit_lut() -> KtanhLut:
     st = load_library().ktanh_fit_lut(ctypes.byref(lut))
     if st != 0:
         raise KtanhError(st, "ktanh_fit_lut")
+    return lut
+
+
+def ktanh_fit_lut_bmin0() -> KtanhLut:
+    """The ablation's sub-optimal table: the fit of Section 2.4 with b_min = 0."""
+    lut = KtanhLut()
+    st = load_library().ktanh_fit_lut_bmin0(ctypes.byref(lut))
+    if st != 0:
+        raise KtanhError(st, "ktanh_fit_lut_bmin0")
     return lut
 
 

@@ -61,7 +61,8 @@ double pinned_mantissa(const Sample &s, int E)
     return E > s.exponent ? 0.0 : double((1 << kOutMantissaBits) - 1);
 }
 
-Fit fit_interval(int t, int index_bits)
+// offsets_add_only: the ablation of Section 3, which sets b_min = 0.
+Fit fit_interval(int t, int index_bits, bool offsets_add_only = false)
 {
     const std::vector<Sample> pts = interval_samples(t, index_bits);
     const int mantissa_idx_val = t & ((1 << index_bits) - 1);
@@ -91,7 +92,7 @@ Fit fit_interval(int t, int index_bits)
         const long last_m = (long)(mantissa_idx_val + 1) * per - 1;
         const long b_max = (1L << kMantissaBits) - 1 - (last_m >> r);
         const int width = kMantissaBits - index_bits - r;
-        const long b_min = -(long)mantissa_idx_val * (width >= 0 ? (1L << width) : 0L);
+        const long b_min = offsets_add_only ? 0L : -(long)mantissa_idx_val * (width >= 0 ? (1L << width) : 0L);
         if (b < b_min) b = b_min;
         if (b > b_max) b = b_max;
         double obj = 0.0;
@@ -111,6 +112,18 @@ extern "C" ktanh_status_t ktanh_fit_lut(ktanh_lut_t *out)
     if (out == nullptr) return KT_ERR_NULL;
     for (int t = 0; t < KTANH_INTERVALS; ++t) {
         const Fit f = fit_interval(t, 3);
+        out->E[t] = (uint8_t)f.E;
+        out->r[t] = (uint8_t)f.r;
+        out->b[t] = (int8_t)f.b;
+    }
+    return KT_OK;
+}
+
+extern "C" ktanh_status_t ktanh_fit_lut_bmin0(ktanh_lut_t *out)
+{
+    if (out == nullptr) return KT_ERR_NULL;
+    for (int t = 0; t < KTANH_INTERVALS; ++t) {
+        const Fit f = fit_interval(t, 3, true);
         out->E[t] = (uint8_t)f.E;
         out->r[t] = (uint8_t)f.r;
         out->b[t] = (int8_t)f.b;

@@ -102,8 +102,11 @@ def test_library_fit_reproduces_table1_and_matches_the_oracle_fit64(binding, ora
     lut64 = binding.ktanh_fit_lut64()
     assert lut64.as_tuples() == oracle.fit_lut64().as_tuples()
     assert binding.ktanh_lut64_validate(lut64) == 0
+    ablation = binding.ktanh_fit_lut_bmin0()
+    assert ablation.as_tuples() == oracle.fit_lut_bmin0().as_tuples()
+    assert binding.ktanh_lut_validate(ablation) == 0
     lib = binding.load_library()
-    assert lib.ktanh_fit_lut(None) == 1 and lib.ktanh_fit_lut64(None) == 1
+    assert lib.ktanh_fit_lut(None) == 1 and lib.ktanh_fit_lut64(None) == 1 and lib.ktanh_fit_lut_bmin0(None) == 1
 
 
 def test_lut64_validation(binding):

@@ -465,6 +465,16 @@ def _random_valid_table(rng, intervals):
     return rows
 
 
+def test_ablation_table_on_the_gpu(gpu, oracle):
+    """The b_min = 0 table of the ablation study, fitted by the library, fed to the kernels."""
+    binding, torch = gpu
+    klut, olut = binding.ktanh_fit_lut_bmin0(), oracle.fit_lut_bmin0()
+    x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(100003, seed=62)])
+    for name in BF16_OPS:
+        got = _to_host(getattr(binding, name)(_to_dev(torch, x), lut=klut), np.uint16)
+        _assert_bf16_equal(got, getattr(oracle, name)(x, olut), name == "ktanh_bf16", name + " ablation table")
+
+
 def test_random_valid_tables(gpu, oracle):
     """The packed slots (folded input exponent, saturation slot, Float32 base) must reproduce
     Algorithm 1 for every table the validator lets through, not just for Table 1."""
