@@ -662,3 +662,74 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
     _assert_bf16_equal(_to_host(g[1].grad.view(torch.int16), np.uint16).ravel(), dg2_ref.ravel(), False, "dgates step 2")
     _assert_bf16_equal(_to_host(g[0].grad.view(torch.int16), np.uint16).ravel(), dg1_ref.ravel(), False, "dgates step 1")
     assert np.array_equal(c0d.grad.cpu().numpy().view(np.uint32), dc0_ref.view(np.uint32))
+
+
+# ------------------------------------------------------------------ random sizes and alignments
+def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, oracle):
+    """300 seeded draws of (entry point, n, offset of each tensor): the peeled heads and tails, the
+    switch to the element-wise kernel on mismatched alignment, and the guard bands around the output
+    must hold for any of them, not only for the hand-picked cases above."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(63))
+    N = 40000
+    xb = np.concatenate([wl.all_bf16_patterns()[rng.permutation(1 << 16)[: N // 2]],
+                         wl.mlp_preactivations(N - N // 2 + 64, seed=64)])
+    db = wl.f32_to_bf16_bits(rng.standard_normal(xb.size, dtype=np.float32))
+    xu = np.concatenate([rng.integers(0, 1 << 32, size=N // 2, dtype=np.uint64).astype(np.uint32),
+                         wl.f32_mixture(N - N // 2 + 64, seed=65)])
+    xf = xu.view(np.float32)
+    xbd, dbd, xud = _to_dev(torch, xb), _to_dev(torch, db), _to_dev(torch, xu)
+    xfd = xud.view(torch.float32)
+    with np.errstate(all="ignore"):
+        yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
+        cases = {
+            "ktanh_bf16": ("bf16", yb), "ksigmoid": ("bf16", sb), "kswish": ("bf16", oracle.kswish(xb)),
+            "kgelu": ("bf16", oracle.kgelu(xb)), "ktanh64_bf16": ("bf16", oracle.ktanh64_bf16(xb)),
+            "ksigmoid64": ("bf16", oracle.ksigmoid64(xb)), "kswish64": ("bf16", oracle.kswish64(xb)),
+            "kgelu64": ("bf16", oracle.kgelu64(xb)),
+            "ktanh_f32": ("u32", oracle.ktanh_f32(xu)), "ktanh64_f32": ("u32", oracle.ktanh64_f32(xu)),
+            "ksigmoid_f32": ("f32", oracle.ksigmoid_f32(xf)), "kswish_f32": ("f32", oracle.kswish_f32(xf)),
+            "kgelu_f32": ("f32", oracle.kgelu_f32(xf)),
+            "ktanh_f32_to_bf16": ("f32->bf16", oracle.ktanh_f32_to_bf16(xf)),
+            "ktanh_bf16_backward": ("grad", oracle.ktanh_backward(db, yb)),
+            "ksigmoid_backward": ("grad", oracle.ksigmoid_backward(db, sb)),
+            "kswish_backward": ("grad", oracle.kswish_backward(db, xb)),
+            "kgelu_backward": ("grad", oracle.kgelu_backward(db, xb)),
+        }
+    ybd, sbd = _to_dev(torch, yb), _to_dev(torch, sb)
+    names = sorted(cases)
+    for trial in range(300):
+        name = names[int(rng.integers(len(names)))]
+        kind, want = cases[name]
+        n = int(rng.choice([int(rng.integers(1, 40)), int(rng.integers(40, 3000)), int(rng.integers(3000, N))]))
+        a, o, g = (int(v) for v in rng.integers(0, 17, size=3))      # element offsets of in, out, dy
+        a = min(a, xb.size - n)
+        what = f"trial {trial}: {name} n={n} offsets in={a} out={o} dy={g}"
+        fn = getattr(binding, name)
+        if kind in ("bf16", "grad", "f32->bf16"):
+            guard = torch.full((n + 48,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+            out = guard[16 + o:16 + o + n]
+            if kind == "bf16":
+                fn(xbd[a:a + n], out=out)
+            elif kind == "f32->bf16":
+                fn(xfd[a:a + n], out=out)
+            else:
+                # dy needs its own offset: a shifted copy of the slice the expected values were made from
+                dyd = torch.empty(n + 32, dtype=torch.int16, device="cuda:0")
+                dyd[g:g + n] = dbd[a:a + n]
+                second = {"ktanh_bf16_backward": ybd, "ksigmoid_backward": sbd}.get(name, xbd)
+                fn(dyd[g:g + n], second[a:a + n], dx=out)
+            res = _to_host(guard, np.uint16)
+            _assert_bf16_equal(res[16 + o:16 + o + n], want[a:a + n], False, what)
+            assert np.all(res[:16 + o] == 0x5A5A) and np.all(res[16 + o + n:] == 0x5A5A), what
+        else:
+            guard = torch.full((n + 48,), 0x5A5A5A5A, dtype=torch.int32, device="cuda:0")
+            if kind == "u32":
+                fn(xud[a:a + n], out=guard[16 + o:16 + o + n])
+                res = guard.cpu().numpy().view(np.uint32)
+                assert np.array_equal(res[16 + o:16 + o + n], want[a:a + n]), what
+            else:
+                fn(xfd[a:a + n], out=guard.view(torch.float32)[16 + o:16 + o + n])
+                res = guard.cpu().numpy().view(np.uint32)
+                _assert_f32_equal(res[16 + o:16 + o + n].view(np.float32), want[a:a + n], what)
+            assert np.all(res[:16 + o] == 0x5A5A5A5A) and np.all(res[16 + o + n:] == 0x5A5A5A5A), what
