@@ -25,7 +25,7 @@
  *                          K-TanH on BFloat16 inputs that arrive as Float32:
  *                          the Float32 -> BFloat16 conversion that Section 2.5
  *                          leaves out of its cycle count, then Algorithm 1
- *   oracle_ksigmoid_f32/kswish_f32/kgelu_f32
+ *   oracle_ksigmoid_f32/kswish_f32/kgelu_f32 (and their ...64_f32 forms)
  *                          the Section 1 identities on Float32 tensors with
  *                          the Float32 form of Algorithm 1 inside (the paper
  *                          prints nothing for these: pinned through the
@@ -37,7 +37,9 @@
  *                          trains GNMT with it; the paper does not say how
  *                          the gradient is formed): the derivative identities
  *                          of TanH and Sigmoid, dy*(1-y^2) and dy*s*(1-s),
- *                          evaluated on the K-TanH outputs.  Parity unpinned by
+ *                          evaluated on the K-TanH outputs, and the derivatives
+ *                          of the Swish and GELU identities with the K-TanH
+ *                          value rebuilt from the input.  Parity unpinned by
  *                          the paper; pinned by double re-evaluation, by the
  *                          distance to the exact derivatives, and by hand
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
@@ -456,43 +458,66 @@ void oracle_klstm_cell64(const uint16_t *gates, const float *c_in, float *c_out,
 static float f32_of_bits(uint32_t u) { float f; memcpy(&f, &u, sizeof f); return f; }
 static uint32_t bits_of_f32(float f) { uint32_t u; memcpy(&u, &f, sizeof u); return u; }
 
-static float ksigmoid_f32_scalar(float x, const oracle_lut *lut)
+static float ksigmoid_f32_fields(float x, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                 const int8_t *Tb)
 {
     float half_x = 0.5f * x;
-    float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(half_x), lut));
+    float th = f32_of_bits(ktanh_f32_fields(bits_of_f32(half_x), s, TE, Tr, Tb));
     float half_th = 0.5f * th;
     return half_th + 0.5f;
 }
 
+static float kgelu_f32_fields(float x, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                              const int8_t *Tb)
+{
+    const float a = 0.044715f;
+    const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
+    float x2 = x * x;
+    float x3 = x2 * x;
+    float ax3 = a * x3;
+    float inner = x + ax3;
+    float arg = c * inner;
+    float th = f32_of_bits(ktanh_f32_fields(bits_of_f32(arg), s, TE, Tr, Tb));
+    float half_x = 0.5f * x;
+    float one_plus = 1.0f + th;
+    return half_x * one_plus;
+}
+
 void oracle_ksigmoid_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
 {
-    for (size_t i = 0; i < n; ++i) out[i] = ksigmoid_f32_scalar(in[i], lut);
+    for (size_t i = 0; i < n; ++i) out[i] = ksigmoid_f32_fields(in[i], 3, lut->E, lut->r, lut->b);
 }
 
 void oracle_kswish_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
 {
     for (size_t i = 0; i < n; ++i) {
-        float sg = ksigmoid_f32_scalar(in[i], lut);
+        float sg = ksigmoid_f32_fields(in[i], 3, lut->E, lut->r, lut->b);
         out[i] = in[i] * sg;
     }
 }
 
 void oracle_kgelu_f32(const float *in, float *out, size_t n, const oracle_lut *lut)
 {
-    const float a = 0.044715f;
-    const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
+    for (size_t i = 0; i < n; ++i) out[i] = kgelu_f32_fields(in[i], 3, lut->E, lut->r, lut->b);
+}
+
+/* The same three on 64-interval tables. */
+void oracle_ksigmoid64_f32(const float *in, float *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = ksigmoid_f32_fields(in[i], 4, lut->E, lut->r, lut->b);
+}
+
+void oracle_kswish64_f32(const float *in, float *out, size_t n, const oracle_lut64 *lut)
+{
     for (size_t i = 0; i < n; ++i) {
-        float x = in[i];
-        float x2 = x * x;
-        float x3 = x2 * x;
-        float ax3 = a * x3;
-        float inner = x + ax3;
-        float arg = c * inner;
-        float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(arg), lut));
-        float half_x = 0.5f * x;
-        float one_plus = 1.0f + th;
-        out[i] = half_x * one_plus;
+        float sg = ksigmoid_f32_fields(in[i], 4, lut->E, lut->r, lut->b);
+        out[i] = in[i] * sg;
     }
+}
+
+void oracle_kgelu64_f32(const float *in, float *out, size_t n, const oracle_lut64 *lut)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = kgelu_f32_fields(in[i], 4, lut->E, lut->r, lut->b);
 }
 
 /* Float32 in, BFloat16 out: round to nearest even, then Algorithm 1 on BFloat16. */

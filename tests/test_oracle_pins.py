@@ -534,6 +534,38 @@ def test_derived_ops_on_64_interval_tables(oracle):
     assert np.array_equal(c_a, c_b) and np.array_equal(h_a, h_b)
 
 
+def test_f32_derived_ops_on_64_interval_tables(oracle):
+    """Float32-tensor activations around the 64-interval Float32 K-TanH (pinned above): a table that
+    repeats Table 1's entries must give the 32-interval results bit for bit, the fitted table must
+    agree with float64 re-evaluation, and three values by hand."""
+    doubled = oracle.OracleLut64.from_tuples([oracle.table1().as_tuples()[((t >> 4) << 3) | ((t & 15) >> 1)] for t in range(64)])
+    rng = np.random.Generator(np.random.PCG64(36))
+    u = np.concatenate([np.arange(1 << 16, dtype=np.uint32) << 16,
+                        rng.integers(0, 1 << 32, size=1 << 18, dtype=np.uint64).astype(np.uint32),
+                        wl.f32_mixture(1 << 18, seed=37)])
+    u = u[(u & 0x7FFFFFFF) < 0x7F800000]
+    xf = u.view(np.float32)
+    with np.errstate(all="ignore"):
+        for name in ("ksigmoid", "kswish", "kgelu"):
+            a = getattr(oracle, name + "64_f32")(xf, doubled)
+            b = getattr(oracle, name + "_f32")(xf)
+            same = (a.view(np.uint32) == b.view(np.uint32)) | (np.isnan(a) & np.isnan(b))
+            assert np.all(same), name
+        xv = xf.astype(np.float64)
+        k = oracle.ktanh64_f32(np.ascontiguousarray((xf * np.float32(0.5))).view(np.uint32)).view(np.float32).astype(np.float64)
+        sig = 0.5 + 0.5 * k
+        got = oracle.ksigmoid64_f32(xf).astype(np.float64)
+        assert np.max(np.abs(got - sig)) <= 2.0 ** -24
+        sw = oracle.kswish64_f32(xf).astype(np.float64)
+        ok = np.abs(xv * sig) < 3.0e38
+        assert np.max(np.abs(sw[ok] - (xv * sig)[ok]) - 2.0 ** -23 * np.abs((xv * sig)[ok])) <= 1e-45
+    # x = 1: K64(0.5) = 0.466796875 (entry 32 = (125, 0, 111), see above); (1 + K)/2 = 0.7333984375
+    assert oracle.ksigmoid64_f32(np.array([1.0], np.float32))[0] == np.float32(0.7333984375)
+    # GELU at x = 4: the argument saturates, 2 * (1 + 1) = 4;  at x = -4: -2 * 0 = -0
+    out = oracle.kgelu64_f32(np.array([4.0, -4.0], np.float32))
+    assert out[0] == np.float32(4.0) and out[1] == 0 and np.signbit(out[1])
+
+
 # ---------------------------------------------------------------- gradients
 def test_backward_of_ktanh_and_ksigmoid(oracle):
     """dy * (1 - y^2) and dy * s * (1 - s) on the forward outputs: float64 re-evaluation to 1 ulp,
