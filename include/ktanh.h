@@ -160,6 +160,13 @@ ktanh_status_t kswish_f32(const float *in, float *out, size_t n, const ktanh_lut
                           ktanh_stream_t stream);
 ktanh_status_t kgelu_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
                          ktanh_stream_t stream);
+/* The same three with a 64-interval table (ktanh64_f32 inside); `lut` == NULL selects the fitted one. */
+ktanh_status_t ksigmoid64_f32(const float *in, float *out, size_t n, const ktanh_lut64_t *lut,
+                              ktanh_stream_t stream);
+ktanh_status_t kswish64_f32(const float *in, float *out, size_t n, const ktanh_lut64_t *lut,
+                            ktanh_stream_t stream);
+ktanh_status_t kgelu64_f32(const float *in, float *out, size_t n, const ktanh_lut64_t *lut,
+                           ktanh_stream_t stream);
 
 /* K-TanH on BFloat16 inputs that arrive as Float32: each value is rounded to BFloat16 (nearest even)
  * and goes through ktanh_bf16 -- the conversion Section 2.5 leaves out of the paper's cycle count,

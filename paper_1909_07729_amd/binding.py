@@ -22,7 +22,8 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
            "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
            "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
-           "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0")
+           "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0",
+           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32")
 
 
 class KtanhLut(ctypes.Structure):
@@ -108,7 +109,8 @@ def load_library() -> ctypes.CDLL:
         lib.ktanh_fit_lut64.restype = ctypes.c_int
         lib.ktanh_lut64_validate.argtypes = [lp64]
         lib.ktanh_lut64_validate.restype = ctypes.c_int
-        for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64"):
+        for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64",
+                     "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, sz, lp64, vp]
             fn.restype = ctypes.c_int
@@ -158,7 +160,8 @@ def ktanh_fit_lut_bmin0() -> KtanhLut:
     lut = KtanhLut()
     st = load_library().ktanh_fit_lut_bmin0(ctypes.byref(lut))
     if st != 0:
-        raise KtanhError(st, "ktanh_fit_lut_bmin0")
+        raise KtanhError(st, "ktanh_fit_lut_bmin0",
+           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32")
     return lut
 
 
@@ -266,6 +269,19 @@ def kswish_f32(x, out=None, lut=None, stream=None):
 
 def kgelu_f32(x, out=None, lut=None, stream=None):
     return _elementwise("kgelu_f32", x, out, lut, stream, (torch.float32,))
+
+
+def ksigmoid64_f32(x, out=None, lut=None, stream=None):
+    """Sigmoid on a Float32 tensor through the Float32 K-TanH with a 64-interval table."""
+    return _elementwise("ksigmoid64_f32", x, out, lut, stream, (torch.float32,))
+
+
+def kswish64_f32(x, out=None, lut=None, stream=None):
+    return _elementwise("kswish64_f32", x, out, lut, stream, (torch.float32,))
+
+
+def kgelu64_f32(x, out=None, lut=None, stream=None):
+    return _elementwise("kgelu64_f32", x, out, lut, stream, (torch.float32,))
 
 
 def ktanh_f32_to_bf16(x, out=None, lut=None, stream=None):

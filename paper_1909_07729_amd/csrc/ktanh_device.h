@@ -272,12 +272,11 @@ __device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
 template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &tab)
 {
-    static_assert(!WIDE || OP == OP_TANH, "Float32-tensor activations exist for 32 intervals only");
     if constexpr (OP == OP_TANH) {
         return ktanh_f32_one<WIDE>(u, tab);
     } else if constexpr (OP == OP_SIGMOID || OP == OP_SWISH) {
         const float x = __uint_as_float(u);
-        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * x), tab));
+        const float t = __uint_as_float(ktanh_f32_one<WIDE>(__float_as_uint(0.5f * x), tab));
         const float sg = __builtin_fmaf(0.5f, t, 0.5f);
         return __float_as_uint(OP == OP_SIGMOID ? sg : x * sg);
     } else {
@@ -285,7 +284,7 @@ __device__ __forceinline__ uint32_t apply_f32_one(uint32_t u, const LaneTable &t
         const float c = 0.7978845608028654f;
         const float x = __uint_as_float(u);
         const float arg = c * (x + a * ((x * x) * x));
-        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(arg), tab));
+        const float t = __uint_as_float(ktanh_f32_one<WIDE>(__float_as_uint(arg), tab));
         return __float_as_uint(x * __builtin_fmaf(0.5f, t, 0.5f));
     }
 }

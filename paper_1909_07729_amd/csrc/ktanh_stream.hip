@@ -344,3 +344,21 @@ extern "C" ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size
                           kBlock, stream, reinterpret_cast<const uint32_t *>(in), out,
                           (unsigned long long)n, pack);
 }
+
+extern "C" ktanh_status_t ksigmoid64_f32(const float *in, float *out, size_t n,
+                                         const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SIGMOID>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish64_f32(const float *in, float *out, size_t n,
+                                       const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_SWISH>(in, out, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu64_f32(const float *in, float *out, size_t n,
+                                      const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_elementwise<true, OP_GELU>(in, out, n, lut, stream);
+}

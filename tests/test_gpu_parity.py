@@ -360,6 +360,21 @@ def test_f32_derived_ops(gpu, oracle, name):
         _assert_f32_equal(xd.cpu().numpy(), getattr(oracle, name)(xf[: n + 8]), name + " in place")
 
 
+def test_f32_derived_ops_on_64_interval_tables(gpu, oracle):
+    """ksigmoid64_f32, kswish64_f32, kgelu64_f32 on the fitted table and on random valid tables."""
+    binding, torch = gpu
+    xf = _f32_cases().view(np.float32)
+    xd = torch.from_numpy(xf).to("cuda:0")
+    rng = np.random.Generator(np.random.PCG64(66))
+    for rows in (None, _random_valid_table(rng, 64), _random_valid_table(rng, 64)):
+        k64 = binding.KtanhLut64.from_tuples(rows) if rows else None
+        o64 = oracle.OracleLut64.from_tuples(rows) if rows else None
+        for name in ("ksigmoid64_f32", "kswish64_f32", "kgelu64_f32"):
+            with np.errstate(all="ignore"):
+                want = getattr(oracle, name)(xf, o64)
+            _assert_f32_equal(getattr(binding, name)(xd, lut=k64).cpu().numpy(), want, name)
+
+
 def test_f32_to_bf16(gpu, oracle):
     binding, torch = gpu
     u = _f32_cases()
@@ -690,6 +705,8 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             "ktanh_f32": ("u32", oracle.ktanh_f32(xu)), "ktanh64_f32": ("u32", oracle.ktanh64_f32(xu)),
             "ksigmoid_f32": ("f32", oracle.ksigmoid_f32(xf)), "kswish_f32": ("f32", oracle.kswish_f32(xf)),
             "kgelu_f32": ("f32", oracle.kgelu_f32(xf)),
+            "ksigmoid64_f32": ("f32", oracle.ksigmoid64_f32(xf)), "kswish64_f32": ("f32", oracle.kswish64_f32(xf)),
+            "kgelu64_f32": ("f32", oracle.kgelu64_f32(xf)),
             "ktanh_f32_to_bf16": ("f32->bf16", oracle.ktanh_f32_to_bf16(xf)),
             "ktanh_bf16_backward": ("grad", oracle.ktanh_backward(db, yb)),
             "ksigmoid_backward": ("grad", oracle.ksigmoid_backward(db, sb)),
