@@ -32,7 +32,7 @@
  *                          BFloat16 operations where the two must coincide,
  *                          and by double-precision re-evaluation)
  *   oracle_ktanh_backward, oracle_ksigmoid_backward, oracle_klstm_cell_backward,
- *   oracle_kswish_backward, oracle_kgelu_backward
+ *   oracle_kswish_backward, oracle_kgelu_backward, and the four ..._f32_backward
  *                          gradients for training through K-TanH (Section 3
  *                          trains GNMT with it; the paper does not say how
  *                          the gradient is formed): the derivative identities
@@ -601,6 +601,68 @@ void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, 
         float slope = left + right;
         float g = widen(dy[i]) * slope;
         dx[i] = narrow_rne(g);
+    }
+}
+
+/* The same four gradients on Float32 tensors: nothing is rounded to BFloat16, the
+ * K-TanH inside Swish and GELU is the Float32 form of Algorithm 1. */
+void oracle_ktanh_f32_backward(const float *dy, const float *y, float *dx, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float y2 = y[i] * y[i];
+        float slope = 1.0f - y2;
+        dx[i] = dy[i] * slope;
+    }
+}
+
+void oracle_ksigmoid_f32_backward(const float *dy, const float *sg, float *dx, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float one_minus = 1.0f - sg[i];
+        float slope = sg[i] * one_minus;
+        dx[i] = dy[i] * slope;
+    }
+}
+
+void oracle_kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                const oracle_lut *lut)
+{
+    for (size_t i = 0; i < n; ++i) {
+        float sg = ksigmoid_f32_fields(x[i], 3, lut->E, lut->r, lut->b);
+        float one_minus = 1.0f - sg;
+        float bell = sg * one_minus;
+        float xbell = x[i] * bell;
+        float slope = sg + xbell;
+        dx[i] = dy[i] * slope;
+    }
+}
+
+void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                               const oracle_lut *lut)
+{
+    const float a = 0.044715f;
+    const float a3 = 0.134145f;
+    const float c = (float)0.7978845608028654; /* sqrt(2/pi) */
+    for (size_t i = 0; i < n; ++i) {
+        float xv = x[i];
+        float x2 = xv * xv;
+        float x3 = x2 * xv;
+        float ax3 = a * x3;
+        float inner = xv + ax3;
+        float arg = c * inner;
+        float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(arg), lut));
+        float one_plus = 1.0f + th;
+        float left = 0.5f * one_plus;
+        float th2 = th * th;
+        float sech2 = 1.0f - th2;
+        float a3x2 = a3 * x2;
+        float poly = 1.0f + a3x2;
+        float du = c * poly;
+        float chain = sech2 * du;
+        float half_x = 0.5f * xv;
+        float right = half_x * chain;
+        float slope = left + right;
+        dx[i] = dy[i] * slope;
     }
 }
 

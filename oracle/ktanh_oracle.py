@@ -103,6 +103,12 @@ def _load():
         for name in ("oracle_ktanh_backward", "oracle_ksigmoid_backward"):
             getattr(lib, name).argtypes = [vp, vp, vp, sz]
             getattr(lib, name).restype = None
+        for name in ("oracle_ktanh_f32_backward", "oracle_ksigmoid_f32_backward"):
+            getattr(lib, name).argtypes = [vp, vp, vp, sz]
+            getattr(lib, name).restype = None
+        for name in ("oracle_kswish_f32_backward", "oracle_kgelu_f32_backward"):
+            getattr(lib, name).argtypes = [vp, vp, vp, sz, lp]
+            getattr(lib, name).restype = None
         for name in ("oracle_kswish_backward", "oracle_kgelu_backward"):
             getattr(lib, name).argtypes = [vp, vp, vp, sz, lp]
             getattr(lib, name).restype = None
@@ -338,6 +344,39 @@ def kswish_backward(dy_bits, x_bits, lut=None):
 def kgelu_backward(dy_bits, x_bits, lut=None):
     """dx = dy * GELU'(x) of the tanh form with K-TanH inside, from the forward INPUT x."""
     return _backward_from_input("oracle_kgelu_backward", dy_bits, x_bits, lut)
+
+
+def _f32_backward(name, dy, v, lut=None, with_lut=False):
+    dy = np.ascontiguousarray(dy, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    assert dy.shape == v.shape
+    dx = np.empty_like(dy)
+    if with_lut:
+        lut = table1() if lut is None else lut
+        getattr(_load(), name)(dy.ctypes.data, v.ctypes.data, dx.ctypes.data, dy.size, ctypes.byref(lut))
+    else:
+        getattr(_load(), name)(dy.ctypes.data, v.ctypes.data, dx.ctypes.data, dy.size)
+    return dx
+
+
+def ktanh_f32_backward(dy, y):
+    """dx = dy * (1 - y^2), float32 throughout; y = the forward Float32 K-TanH output."""
+    return _f32_backward("oracle_ktanh_f32_backward", dy, y)
+
+
+def ksigmoid_f32_backward(dy, s):
+    """dx = dy * s * (1 - s), float32 throughout; s = the forward ksigmoid_f32 output."""
+    return _f32_backward("oracle_ksigmoid_f32_backward", dy, s)
+
+
+def kswish_f32_backward(dy, x, lut=None):
+    """dx = dy * Swish'(x) from the forward input x, float32 throughout."""
+    return _f32_backward("oracle_kswish_f32_backward", dy, x, lut, True)
+
+
+def kgelu_f32_backward(dy, x, lut=None):
+    """dx = dy * GELU'(x) from the forward input x, float32 throughout."""
+    return _f32_backward("oracle_kgelu_f32_backward", dy, x, lut, True)
 
 
 def klstm_cell_backward(gates_bits, c_prev, dh_bits, dc_next, lut=None):

@@ -682,3 +682,55 @@ def test_backward_of_kswish_and_kgelu(oracle):
     # where the slope nearly cancels (left + right close to 0) the float32 sum keeps fewer bits
     loose = np.abs(_bf16_val(got[ok]) - want[ok]) <= 2.0 ** -8 * np.abs(want[ok]) + 1e-6 * np.abs(dv[ok]) * (1 + np.abs(xv[ok]) ** 3)
     assert np.all(loose)
+
+
+def test_f32_backward_functions(oracle):
+    """The four gradients on Float32 tensors: values by hand, float64 re-evaluation around the pinned
+    Float32 K-TanH, the exact derivatives as closed forms, and slope(x) + slope(-x) = 1."""
+    one = np.ones(4, np.float32)
+    # 1 - 0.75^2 = 0.4375;  2 * 0.75 * 0.25 = 0.375
+    assert np.array_equal(oracle.ktanh_f32_backward(one, np.array([0, 0.75, 1, -1], np.float32)),
+                          np.array([1, 0.4375, 0, 0], np.float32))
+    assert np.array_equal(oracle.ksigmoid_f32_backward(2 * one, np.array([0.75, 0.5, 1, 0], np.float32)),
+                          np.array([0.375, 0.5, 0, 0], np.float32))
+    # Swish' at 0, 1, 8, -8: s = 0.5, 47/64, 1, 0 -> 0.5, 3807/4096 (see the BFloat16 spot value), 1, 0
+    assert np.array_equal(oracle.kswish_f32_backward(one, np.array([0, 1, 8, -8], np.float32)),
+                          np.array([0.5, 3807 / 4096, 1, 0], np.float32))
+    # GELU' at 1: argument 0.8335619 -> entry 21 = (126, 1, 4): mantissa 0.6671238/2 + 4/128 -> t = 0.6824059;
+    # 0.5*(1 + t) + 0.5*(1 - t^2)*0.7978846*1.134145 = 1.0829614
+    ge = oracle.kgelu_f32_backward(one, np.array([0, 1, 4, -4], np.float32))
+    assert ge[0] == 0.5 and abs(float(ge[1]) - 1.0829614) < 2e-6 and ge[2] == 1 and ge[3] == 0
+
+    rng = np.random.Generator(np.random.PCG64(38))
+    xf = np.concatenate([wl.f32_mixture(1 << 18, seed=39).view(np.float32),
+                         rng.standard_normal(1 << 18, dtype=np.float32) * 3,
+                         (np.arange(-4096, 4097, dtype=np.float32) / 256)])
+    dy = rng.standard_normal(xf.size, dtype=np.float32)
+    xv, dv = xf.astype(np.float64), dy.astype(np.float64)
+    kf = lambda v: oracle.ktanh_f32(np.ascontiguousarray(v, dtype=np.float32).view(np.uint32)).view(np.float32).astype(np.float64)
+    y = oracle.ktanh_f32(xf.view(np.uint32)).view(np.float32)
+    s = oracle.ksigmoid_f32(xf)
+    close = lambda got, want: np.max(np.abs(got - want) - 4 * 2.0 ** -24 * (np.abs(want) + np.abs(dv))) <= 0
+    assert close(oracle.ktanh_f32_backward(dy, y), dv * (1 - y.astype(np.float64) ** 2))
+    assert close(oracle.ksigmoid_f32_backward(dy, s), dv * s.astype(np.float64) * (1 - s.astype(np.float64)))
+    s64 = 0.5 + 0.5 * kf(xf * np.float32(0.5))
+    assert close(oracle.kswish_f32_backward(dy, xf), dv * (s64 + xv * (s64 * (1 - s64))))
+    arg32 = np.float32(0.7978845608028654) * (xf + np.float32(0.044715) * ((xf * xf) * xf))
+    t = kf(arg32)
+    want = dv * (0.5 * (1 + t) + 0.5 * xv * ((1 - t * t) * (np.sqrt(2 / np.pi) * (1 + 0.134145 * xv * xv))))
+    got = oracle.kgelu_f32_backward(dy, xf)
+    assert np.max(np.abs(got - want) - 1e-6 * np.abs(dv) * (1 + np.abs(xv) ** 3)) <= 0
+
+    ones = np.ones(xf.size, np.float32)
+    act = np.abs(xv) <= 16
+    sw, sw_n = oracle.kswish_f32_backward(ones, xf).astype(np.float64), oracle.kswish_f32_backward(ones, -xf).astype(np.float64)
+    gl, gl_n = oracle.kgelu_f32_backward(ones, xf).astype(np.float64), oracle.kgelu_f32_backward(ones, -xf).astype(np.float64)
+    assert np.max(np.abs(sw + sw_n - 1)[act]) <= 1e-6 and np.max(np.abs(gl + gl_n - 1)[act]) <= 1e-5
+    s_true = 1 / (1 + np.exp(-xv.clip(-80, 80)))
+    u = np.sqrt(2 / np.pi) * (xv + 0.044715 * xv ** 3)
+    t_true = np.tanh(u)
+    ge_true = 0.5 * (1 + t_true) + 0.5 * xv * (1 - t_true ** 2) * np.sqrt(2 / np.pi) * (1 + 3 * 0.044715 * xv ** 2)
+    assert np.max(np.abs(sw - s_true * (1 + xv * (1 - s_true)))[act]) <= 0.012
+    assert np.max(np.abs(gl - ge_true)[act]) <= 0.03
+    assert np.max(np.abs(oracle.ktanh_f32_backward(ones, y) - (1 - np.tanh(xv) ** 2))) <= 2 * 1.67e-2 + 1e-6
+    assert np.max(np.abs(oracle.ksigmoid_f32_backward(ones, s) - s_true * (1 - s_true))) <= 1.67e-2 / 2 + 1e-6
