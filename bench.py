@@ -223,6 +223,8 @@ def run_extras(torch, binding, wl, upload, xs, ys):
         fn = getattr(binding, name)
         record(name, "same 2^28 fp32 tensor, fp32 in and out, 2 rotating buffer pairs",
                lambda i, fn=fn: fn(x3f[i % 2], out=y3f[i % 2]), x3[0].numel(), 8, 60, 10)
+    record("kgelu_f32_backward", "dy, x and dx of 2^28 fp32 each (12 B per element), dx alternating over 2 buffers",
+           lambda i: binding.kgelu_f32_backward(x3f[1], x3f[0], dx=y3f[i % 2]), x3[0].numel(), 12, 40, 10)
     y3h = [torch.empty(x3[0].numel(), dtype=torch.bfloat16, device=x3[0].device) for _ in range(2)]
     record("ktanh_f32_to_bf16", "same 2^28 fp32 tensor in, bf16 out (conversion fused into the load)",
            lambda i: binding.ktanh_f32_to_bf16(x3f[i % 2], out=y3h[i % 2]), x3[0].numel(), 6, 60, 4)

@@ -219,6 +219,20 @@ ktanh_status_t kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *
 ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
                               const ktanh_lut_t *lut, ktanh_stream_t stream);
 
+/* The same four gradients on Float32 tensors (n elements each, device, 4-byte aligned; pointers
+ * that are all 16-byte aligned take the vector path): the formulas above with nothing rounded to
+ * BFloat16 and, inside Swish and GELU, the Float32 K-TanH of ksigmoid_f32 / kgelu_f32.
+ * y, s: forward outputs of ktanh_f32 / ksigmoid_f32 as Float32 values; x: forward input.
+ * dx may alias dy or the other input. */
+ktanh_status_t ktanh_f32_backward(const float *dy, const float *y, float *dx, size_t n,
+                                  ktanh_stream_t stream);
+ktanh_status_t ksigmoid_f32_backward(const float *dy, const float *s, float *dx, size_t n,
+                                     ktanh_stream_t stream);
+ktanh_status_t kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                   const ktanh_lut_t *lut, ktanh_stream_t stream);
+ktanh_status_t kgelu_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                  const ktanh_lut_t *lut, ktanh_stream_t stream);
+
 /* One klstm_cell step backwards.  The forward activations are recomputed from the gate
  * pre-activations with K-TanH exactly as klstm_cell forms them (i, f, o, g, c' = f*c + i*g,
  * tc = K(bf16(c'))); then, in Float32, one rounding per operation:

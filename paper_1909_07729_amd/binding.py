@@ -23,7 +23,8 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
            "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
            "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0",
-           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32")
+           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward")
 
 
 class KtanhLut(ctypes.Structure):
@@ -110,7 +111,8 @@ def load_library() -> ctypes.CDLL:
         lib.ktanh_lut64_validate.argtypes = [lp64]
         lib.ktanh_lut64_validate.restype = ctypes.c_int
         for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64",
-                     "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32"):
+                     "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, sz, lp64, vp]
             fn.restype = ctypes.c_int
@@ -120,9 +122,13 @@ def load_library() -> ctypes.CDLL:
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, sz, vp]
             fn.restype = ctypes.c_int
-        for name in ("kswish_backward", "kgelu_backward"):
+        for name in ("kswish_backward", "kgelu_backward", "kswish_f32_backward", "kgelu_f32_backward"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, vp, sz, lp, vp]
+            fn.restype = ctypes.c_int
+        for name in ("ktanh_f32_backward", "ksigmoid_f32_backward"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, vp, vp, sz, vp]
             fn.restype = ctypes.c_int
         lib.klstm_cell_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz, lp, vp]
         lib.klstm_cell_backward.restype = ctypes.c_int
@@ -161,7 +167,8 @@ def ktanh_fit_lut_bmin0() -> KtanhLut:
     st = load_library().ktanh_fit_lut_bmin0(ctypes.byref(lut))
     if st != 0:
         raise KtanhError(st, "ktanh_fit_lut_bmin0",
-           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32")
+           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward")
     return lut
 
 
@@ -381,6 +388,43 @@ def kswish_backward(dy, x, dx=None, lut=None, stream=None):
 def kgelu_backward(dy, x, dx=None, lut=None, stream=None):
     """dx = dy * GELU'(x) of the tanh form with K-TanH inside, from the forward input x."""
     return _backward_from_input("kgelu_backward", dy, x, dx, lut, stream)
+
+
+def _backward_f32(name, dy, v, dx, lut, stream, with_lut):
+    for t, what in ((dy, "dy"), (v, "the second input")):
+        _check(t, (torch.float32,), what)
+    if dx is None:
+        dx = torch.empty_like(dy)
+    _check(dx, (torch.float32,), "dx")
+    if not (dy.numel() == v.numel() == dx.numel()):
+        raise ValueError("dy, the second input and dx differ in size")
+    args = [dy.data_ptr(), v.data_ptr(), dx.data_ptr(), dy.numel()]
+    if with_lut:
+        args.append(_lut_arg(lut))
+    st = getattr(load_library(), name)(*args, _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, name)
+    return dx
+
+
+def ktanh_f32_backward(dy, y, dx=None, stream=None):
+    """dx = dy * (1 - y^2) on Float32 tensors; y = the forward ktanh_f32 output viewed as Float32."""
+    return _backward_f32("ktanh_f32_backward", dy, y, dx, None, stream, False)
+
+
+def ksigmoid_f32_backward(dy, s, dx=None, stream=None):
+    """dx = dy * s * (1 - s) on Float32 tensors."""
+    return _backward_f32("ksigmoid_f32_backward", dy, s, dx, None, stream, False)
+
+
+def kswish_f32_backward(dy, x, dx=None, lut=None, stream=None):
+    """dx = dy * Swish'(x) on Float32 tensors, from the forward input x."""
+    return _backward_f32("kswish_f32_backward", dy, x, dx, lut, stream, True)
+
+
+def kgelu_f32_backward(dy, x, dx=None, lut=None, stream=None):
+    """dx = dy * GELU'(x) on Float32 tensors, from the forward input x."""
+    return _backward_f32("kgelu_f32_backward", dy, x, dx, lut, stream, True)
 
 
 def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None):

@@ -220,6 +220,129 @@ ktanh_status_t launch_grad_from_input(const uint16_t *dy, const uint16_t *x, uin
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same four gradients on Float32 tensors (12 bytes per element, four elements per 128-bit access).
+// `v` is the forward output for TanH and Sigmoid and the forward input for Swish and GELU, whose
+// K-TanH value is rebuilt with the Float32 form of Algorithm 1.
+enum GradF32 { GF_TANH = 0, GF_SIGMOID = 1, GF_SWISH = 2, GF_GELU = 3 };
+
+template <int GRAD>
+__device__ __forceinline__ uint32_t grad_f32_one(uint32_t dy_bits, uint32_t v_bits, const LaneTable &tab)
+{
+    const float dy = __uint_as_float(dy_bits), v = __uint_as_float(v_bits);
+    float slope;
+    if constexpr (GRAD == GF_TANH) {
+        const float sq = v * v;
+        slope = 1.0f - sq;
+    } else if constexpr (GRAD == GF_SIGMOID) {
+        const float one_minus = 1.0f - v;
+        slope = v * one_minus;
+    } else if constexpr (GRAD == GF_SWISH) {
+        // 0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * v), tab));
+        const float s = __builtin_fmaf(0.5f, t, 0.5f);
+        const float one_minus = 1.0f - s;
+        const float bell = s * one_minus;
+        const float xbell = v * bell;
+        slope = s + xbell;
+    } else {
+        const float a = 0.044715f;
+        const float a3 = 0.134145f;
+        const float c = 0.7978845608028654f;
+        const float sq = v * v;
+        const float cube = sq * v;
+        const float acube = a * cube;
+        const float inner = v + acube;
+        const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(c * inner), tab));
+        const float one_plus = 1.0f + t;
+        const float left = 0.5f * one_plus;
+        const float tsq = t * t;
+        const float sech2 = 1.0f - tsq;
+        const float a3sq = a3 * sq;
+        const float poly = 1.0f + a3sq;
+        const float du = c * poly;
+        const float chain = sech2 * du;
+        const float half_x = 0.5f * v;
+        const float right = half_x * chain;
+        slope = left + right;
+    }
+    return __float_as_uint(dy * slope);
+}
+
+// One wavefront per block, one 128-bit vector per lane and stream; every lane stays enabled around
+// the table reads; the last block also takes the n % 4 loose elements.
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_f32_stream_kernel(
+    const uint4 *vdy, const uint4 *vv, uint4 *vdx, unsigned long long nvec, const uint32_t *dy,
+    const uint32_t *v, uint32_t *dx, unsigned long long n, KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const bool live = at < nvec;
+    uint4 a = uint4{0u, 0u, 0u, 0u}, b = uint4{0u, 0u, 0u, 0u};
+    if (live) {
+        a = load_stream(vdy + at);
+        b = load_stream(vv + at);
+    }
+    const uint4 r = uint4{grad_f32_one<GRAD>(a.x, b.x, tab), grad_f32_one<GRAD>(a.y, b.y, tab),
+                          grad_f32_one<GRAD>(a.z, b.z, tab), grad_f32_one<GRAD>(a.w, b.w, tab)};
+    if (live) store_stream(vdx + at, r);
+    if (blockIdx.x == gridDim.x - 1) {  // uniform over the block
+        const unsigned long long loose = nvec * 4 + threadIdx.x;
+        const bool some = loose < n;
+        const uint32_t d1 = some ? dy[loose] : 0u, v1 = some ? v[loose] : 0u;
+        const uint32_t r1 = grad_f32_one<GRAD>(d1, v1, tab);
+        if (some) dx[loose] = r1;
+    }
+}
+
+template <int GRAD>
+__global__ __launch_bounds__(kBlock) void grad_f32_element_kernel(const uint32_t *dy,
+                                                                  const uint32_t *v, uint32_t *dx,
+                                                                  unsigned long long n,
+                                                                  KtLutPack pack)
+{
+    const LaneTable tab(pack);
+    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
+    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n; base += stride) {
+        const unsigned long long i = base + threadIdx.x;
+        const bool some = i < n;
+        const uint32_t d1 = some ? dy[i] : 0u, v1 = some ? v[i] : 0u;
+        const uint32_t r1 = grad_f32_one<GRAD>(d1, v1, tab);
+        if (some) dx[i] = r1;
+    }
+}
+
+template <int GRAD>
+ktanh_status_t launch_grad_f32(const float *dy, const float *v, float *dx, size_t n,
+                               const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    if (n == 0) return KT_OK;
+    if (dy == nullptr || v == nullptr || dx == nullptr) return KT_ERR_NULL;
+    const uintptr_t all = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(v) |
+                          reinterpret_cast<uintptr_t>(dx);
+    if (all & 3) return KT_ERR_ALIGN;
+    if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
+    KtLutPack pack;  // TanH and Sigmoid need no table: Table 1 rides along unused
+    const ktanh_status_t st = kt_pack_lut_f32(lut, &pack);
+    if (st != KT_OK) return st;
+    const uint32_t *udy = reinterpret_cast<const uint32_t *>(dy), *uv = reinterpret_cast<const uint32_t *>(v);
+    uint32_t *udx = reinterpret_cast<uint32_t *>(dx);
+    if ((all & 15) == 0) {
+        const size_t nvec = n / 4;
+        size_t tiles = (nvec + kBlock - 1) / kBlock;
+        if (tiles == 0) tiles = 1;
+        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+        return launch_checked(grad_f32_stream_kernel<GRAD>, (unsigned)tiles, kBlock, stream,
+                              reinterpret_cast<const uint4 *>(dy), reinterpret_cast<const uint4 *>(v),
+                              reinterpret_cast<uint4 *>(dx), (unsigned long long)nvec, udy, uv, udx,
+                              (unsigned long long)n, pack);
+    }
+    const size_t want = (n + kBlock - 1) / kBlock;
+    return launch_checked(grad_f32_element_kernel<GRAD>, (unsigned)(want < 8192 ? want : 8192),
+                          kBlock, stream, udy, uv, udx, (unsigned long long)n, pack);
+}
+
+// ---------------------------------------------------------------------------------------------
 // LSTM cell, one step backwards: each lane owns two neighbouring cells (one packed pair per gate).
 // The forward activations are rebuilt with the same device functions the forward kernel uses; the
 // table reads need every lane enabled, so bounds predicate only the memory accesses.
@@ -320,6 +443,30 @@ extern "C" ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, 
                                          size_t n, const ktanh_lut_t *lut, ktanh_stream_t stream)
 {
     return launch_grad_from_input<GRAD_GELU>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t ktanh_f32_backward(const float *dy, const float *y, float *dx, size_t n,
+                                             ktanh_stream_t stream)
+{
+    return launch_grad_f32<GF_TANH>(dy, y, dx, n, nullptr, stream);
+}
+
+extern "C" ktanh_status_t ksigmoid_f32_backward(const float *dy, const float *s, float *dx, size_t n,
+                                                ktanh_stream_t stream)
+{
+    return launch_grad_f32<GF_SIGMOID>(dy, s, dx, n, nullptr, stream);
+}
+
+extern "C" ktanh_status_t kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                              const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad_f32<GF_SWISH>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                             const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad_f32<GF_GELU>(dy, x, dx, n, lut, stream);
 }
 
 extern "C" ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev,

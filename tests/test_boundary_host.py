@@ -192,6 +192,18 @@ def test_gradient_entry_points_reject_bad_arguments(binding):
         assert fn(ctypes.c_void_p(0x1001), fake, fake, 8, None, null) == 2
         assert fn(fake, fake, fake, (1 << 40) + 8, None, null) == 4
         assert fn(fake, fake, fake, 8, ctypes.byref(bad), null) == 3
+    for name in ("ktanh_f32_backward", "ksigmoid_f32_backward"):
+        fn = getattr(lib, name)
+        assert fn(null, null, null, 0, null) == 0
+        assert fn(fake, null, fake, 8, null) == 1
+        assert fn(fake, fake, ctypes.c_void_p(0x1002), 8, null) == 2
+        assert fn(fake, fake, fake, (1 << 40) + 8, null) == 4
+    for name in ("kswish_f32_backward", "kgelu_f32_backward"):
+        fn = getattr(lib, name)
+        assert fn(null, null, null, 0, None, null) == 0
+        assert fn(null, fake, fake, 8, None, null) == 1
+        assert fn(fake, ctypes.c_void_p(0x1001), fake, 8, None, null) == 2
+        assert fn(fake, fake, fake, 8, ctypes.byref(bad), null) == 3
     bw = lib.klstm_cell_backward
     assert bw(null, null, null, null, null, null, 0, 8, None, null) == 0
     assert bw(fake, fake, fake, null, fake, fake, 2, 8, None, null) == 1

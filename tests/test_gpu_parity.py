@@ -612,6 +612,45 @@ def test_backward_of_kswish_and_kgelu(gpu, oracle):
         _assert_bf16_equal(_to_host(over_x, np.uint16), want, False, name + " over x")
 
 
+def test_backward_on_float32_tensors(gpu, oracle):
+    """The four Float32 gradients: structured and random bit patterns as the second input, random
+    upstream gradients, ragged and unaligned views, in place, and a caller's table."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(67))
+    vf = _f32_cases().view(np.float32)
+    dy = rng.standard_normal(vf.size, dtype=np.float32)
+    dy[: 1 << 16] = vf[rng.permutation(1 << 16)]          # non-finite upstream values too
+    vd, dyd = torch.from_numpy(vf).to("cuda:0"), torch.from_numpy(dy).to("cuda:0")
+    rows = _random_valid_table(np.random.Generator(np.random.PCG64(68)), 32)
+    for name in ("ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward"):
+        with np.errstate(all="ignore"):
+            want = getattr(oracle, name)(dy, vf)
+        _assert_f32_equal(getattr(binding, name)(dyd, vd).cpu().numpy(), want, name)
+        if name in ("kswish_f32_backward", "kgelu_f32_backward"):
+            with np.errstate(all="ignore"):
+                want_custom = getattr(oracle, name)(dy, vf, oracle.OracleLut.from_tuples(rows))
+            got = getattr(binding, name)(dyd, vd, lut=binding.KtanhLut.from_tuples(rows))
+            _assert_f32_equal(got.cpu().numpy(), want_custom, name + " custom table")
+        n = 4096 * 3 + 3
+        for off_dy, off_v, off_out in ((0, 0, 0), (1, 1, 1), (0, 1, 2), (3, 0, 0)):
+            outd = torch.full((n + 16,), 7.0, dtype=torch.float32, device="cuda:0")
+            shifted = torch.empty(n + 8, dtype=torch.float32, device="cuda:0")
+            shifted[off_dy:off_dy + n] = dyd[off_v:off_v + n]
+            getattr(binding, name)(shifted[off_dy:off_dy + n], vd[off_v:off_v + n], dx=outd[4 + off_out:4 + off_out + n])
+            res = outd.cpu().numpy()
+            _assert_f32_equal(res[4 + off_out:4 + off_out + n], want[off_v:off_v + n], f"{name} offsets {off_dy},{off_v},{off_out}")
+            assert np.all(res[:4 + off_out] == 7.0) and np.all(res[4 + off_out + n:] == 7.0)
+        for n_small in (1, 3, 4, 5, 255, 256, 257):
+            got = getattr(binding, name)(dyd[:n_small].clone(), vd[:n_small].clone())
+            _assert_f32_equal(got.cpu().numpy(), want[:n_small], f"{name} n={n_small}")
+        over = dyd.clone()
+        getattr(binding, name)(over, vd, dx=over)
+        _assert_f32_equal(over.cpu().numpy(), want, name + " over dy")
+        over = vd.clone()
+        getattr(binding, name)(dyd, over, dx=over)
+        _assert_f32_equal(over.cpu().numpy(), want, name + " over the second input")
+
+
 @pytest.mark.parametrize("B,H", [(1, 8), (5, 24), (3, 2056), (256, 2048)])
 def test_lstm_cell_backward(gpu, oracle, B, H):
     binding, torch = gpu
@@ -681,7 +720,7 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
 
 # ------------------------------------------------------------------ random sizes and alignments
 def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, oracle):
-    """300 seeded draws of (entry point, n, offset of each tensor): the peeled heads and tails, the
+    """400 seeded draws of (entry point, n, offset of each tensor): the peeled heads and tails, the
     switch to the element-wise kernel on mismatched alignment, and the guard bands around the output
     must hold for any of them, not only for the hand-picked cases above."""
     binding, torch = gpu
@@ -693,8 +732,9 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
     xu = np.concatenate([rng.integers(0, 1 << 32, size=N // 2, dtype=np.uint64).astype(np.uint32),
                          wl.f32_mixture(N - N // 2 + 64, seed=65)])
     xf = xu.view(np.float32)
+    df = rng.standard_normal(xf.size, dtype=np.float32)
     xbd, dbd, xud = _to_dev(torch, xb), _to_dev(torch, db), _to_dev(torch, xu)
-    xfd = xud.view(torch.float32)
+    xfd, dfd = xud.view(torch.float32), torch.from_numpy(df).to("cuda:0")
     with np.errstate(all="ignore"):
         yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
         cases = {
@@ -712,10 +752,14 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             "ksigmoid_backward": ("grad", oracle.ksigmoid_backward(db, sb)),
             "kswish_backward": ("grad", oracle.kswish_backward(db, xb)),
             "kgelu_backward": ("grad", oracle.kgelu_backward(db, xb)),
+            "kswish_f32_backward": ("grad32", oracle.kswish_f32_backward(df, xf)),
+            "kgelu_f32_backward": ("grad32", oracle.kgelu_f32_backward(df, xf)),
+            "ktanh_f32_backward": ("grad32", oracle.ktanh_f32_backward(df, xf)),
+            "ksigmoid_f32_backward": ("grad32", oracle.ksigmoid_f32_backward(df, xf)),
         }
     ybd, sbd = _to_dev(torch, yb), _to_dev(torch, sb)
     names = sorted(cases)
-    for trial in range(300):
+    for trial in range(400):
         name = names[int(rng.integers(len(names)))]
         kind, want = cases[name]
         n = int(rng.choice([int(rng.integers(1, 40)), int(rng.integers(40, 3000)), int(rng.integers(3000, N))]))
@@ -741,7 +785,13 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             assert np.all(res[:16 + o] == 0x5A5A) and np.all(res[16 + o + n:] == 0x5A5A), what
         else:
             guard = torch.full((n + 48,), 0x5A5A5A5A, dtype=torch.int32, device="cuda:0")
-            if kind == "u32":
+            if kind == "grad32":
+                dyd = torch.empty(n + 32, dtype=torch.float32, device="cuda:0")
+                dyd[g:g + n] = dfd[a:a + n]
+                fn(dyd[g:g + n], xfd[a:a + n], dx=guard.view(torch.float32)[16 + o:16 + o + n])
+                res = guard.cpu().numpy().view(np.uint32)
+                _assert_f32_equal(res[16 + o:16 + o + n].view(np.float32), want[a:a + n], what)
+            elif kind == "u32":
                 fn(xud[a:a + n], out=guard[16 + o:16 + o + n])
                 res = guard.cpu().numpy().view(np.uint32)
                 assert np.array_equal(res[16 + o:16 + o + n], want[a:a + n]), what
