@@ -4,8 +4,8 @@ TanH and Sigmoid).
 
 Plumbing only: each ``forward`` is one call of a forward entry point, each ``backward`` one call of
 the matching gradient entry point; all arithmetic runs in the library's kernels.  Tensors are
-``torch.bfloat16`` (Float32 for the LSTM cell state), on the GPU.  The gradient is the derivative
-identity of the exact function evaluated on the K-TanH output (``dy * (1 - y^2)``,
+``torch.bfloat16`` or ``torch.float32`` (the LSTM cell takes BFloat16 gates and a Float32 state),
+on the GPU.  The gradient is the derivative identity of the exact function evaluated on the K-TanH output (``dy * (1 - y^2)``,
 ``dy * s * (1 - s)``, and the derivatives of the Swish and GELU identities); the tables get no
 gradient.
 """
@@ -16,58 +16,53 @@ import torch
 from . import binding
 
 
-class _KTanh(torch.autograd.Function):
+def _is_f32(x: torch.Tensor) -> bool:
+    if x.dtype == torch.float32:
+        return True
+    if x.dtype == torch.bfloat16:
+        return False
+    raise TypeError(f"expected a bfloat16 or float32 tensor, got {x.dtype}")
+
+
+class _FromOutput(torch.autograd.Function):
+    """TanH and Sigmoid: the backward needs only the forward output."""
+
     @staticmethod
-    def forward(ctx, x, lut):
-        y = binding.ktanh_bf16(x.contiguous(), lut=lut)
+    def forward(ctx, x, lut, names):
+        fwd_name, bwd_name = names[_is_f32(x)]
+        y = getattr(binding, fwd_name)(x.contiguous(), lut=lut)
         ctx.save_for_backward(y)
+        ctx.bwd_name = bwd_name
         return y
 
     @staticmethod
     def backward(ctx, dy):
         (y,) = ctx.saved_tensors
-        return binding.ktanh_bf16_backward(dy.contiguous(), y), None
+        return getattr(binding, ctx.bwd_name)(dy.contiguous(), y), None, None
 
 
-class _KSigmoid(torch.autograd.Function):
-    @staticmethod
-    def forward(ctx, x, lut):
-        s = binding.ksigmoid(x.contiguous(), lut=lut)
-        ctx.save_for_backward(s)
-        return s
+class _FromInput(torch.autograd.Function):
+    """Swish and GELU: the backward rebuilds the K-TanH value from the forward input."""
 
     @staticmethod
-    def backward(ctx, dy):
-        (s,) = ctx.saved_tensors
-        return binding.ksigmoid_backward(dy.contiguous(), s), None
-
-
-class _KSwish(torch.autograd.Function):
-    @staticmethod
-    def forward(ctx, x, lut):
+    def forward(ctx, x, lut, names):
+        fwd_name, bwd_name = names[_is_f32(x)]
         x = x.contiguous()
         ctx.save_for_backward(x)
-        ctx.lut = lut
-        return binding.kswish(x, lut=lut)
+        ctx.lut, ctx.bwd_name = lut, bwd_name
+        return getattr(binding, fwd_name)(x, lut=lut)
 
     @staticmethod
     def backward(ctx, dy):
         (x,) = ctx.saved_tensors
-        return binding.kswish_backward(dy.contiguous(), x, lut=ctx.lut), None
+        return getattr(binding, ctx.bwd_name)(dy.contiguous(), x, lut=ctx.lut), None, None
 
 
-class _KGelu(torch.autograd.Function):
-    @staticmethod
-    def forward(ctx, x, lut):
-        x = x.contiguous()
-        ctx.save_for_backward(x)
-        ctx.lut = lut
-        return binding.kgelu(x, lut=lut)
-
-    @staticmethod
-    def backward(ctx, dy):
-        (x,) = ctx.saved_tensors
-        return binding.kgelu_backward(dy.contiguous(), x, lut=ctx.lut), None
+# (forward entry point, gradient entry point) for BFloat16 [False] and Float32 [True] tensors
+_TANH = {False: ("ktanh_bf16", "ktanh_bf16_backward"), True: ("ktanh_f32", "ktanh_f32_backward")}
+_SIGMOID = {False: ("ksigmoid", "ksigmoid_backward"), True: ("ksigmoid_f32", "ksigmoid_f32_backward")}
+_SWISH = {False: ("kswish", "kswish_backward"), True: ("kswish_f32", "kswish_f32_backward")}
+_GELU = {False: ("kgelu", "kgelu_backward"), True: ("kgelu_f32", "kgelu_f32_backward")}
 
 
 class _KLstmCell(torch.autograd.Function):
@@ -93,23 +88,23 @@ class _KLstmCell(torch.autograd.Function):
 
 
 def ktanh(x: torch.Tensor, lut=None) -> torch.Tensor:
-    """K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
-    return _KTanh.apply(x, lut)
+    """K-TanH of a BFloat16 or Float32 tensor, differentiable with respect to ``x``."""
+    return _FromOutput.apply(x, lut, _TANH)
 
 
 def ksigmoid(x: torch.Tensor, lut=None) -> torch.Tensor:
-    """Sigmoid through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
-    return _KSigmoid.apply(x, lut)
+    """Sigmoid through K-TanH of a BFloat16 or Float32 tensor, differentiable with respect to ``x``."""
+    return _FromOutput.apply(x, lut, _SIGMOID)
 
 
 def kswish(x: torch.Tensor, lut=None) -> torch.Tensor:
-    """Swish through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
-    return _KSwish.apply(x, lut)
+    """Swish through K-TanH of a BFloat16 or Float32 tensor, differentiable with respect to ``x``."""
+    return _FromInput.apply(x, lut, _SWISH)
 
 
 def kgelu(x: torch.Tensor, lut=None) -> torch.Tensor:
-    """GELU (tanh form) through K-TanH of a BFloat16 tensor, differentiable with respect to ``x``."""
-    return _KGelu.apply(x, lut)
+    """GELU (tanh form) through K-TanH of a BFloat16 or Float32 tensor, differentiable with respect to ``x``."""
+    return _FromInput.apply(x, lut, _GELU)
 
 
 def klstm_cell(gates: torch.Tensor, c_prev: torch.Tensor, lut=None):

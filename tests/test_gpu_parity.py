@@ -698,6 +698,20 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
         _assert_bf16_equal(_to_host(xd.grad.view(torch.int16), np.uint16), bwd(dy, x if from_input else y_ref),
                            False, fn.__name__ + " grad")
 
+    # the same four functions on Float32 tensors
+    xf = wl.f32_mixture(40009, seed=69).view(np.float32)
+    dyf = rng.standard_normal(xf.size, dtype=np.float32)
+    for fn, fwd, bwd, from_input in ((kt.ktanh, lambda v: oracle.ktanh_f32(v.view(np.uint32)).view(np.float32), oracle.ktanh_f32_backward, False),
+                                     (kt.ksigmoid, oracle.ksigmoid_f32, oracle.ksigmoid_f32_backward, False),
+                                     (kt.kswish, oracle.kswish_f32, oracle.kswish_f32_backward, True),
+                                     (kt.kgelu, oracle.kgelu_f32, oracle.kgelu_f32_backward, True)):
+        xd = torch.from_numpy(xf).to("cuda:0").requires_grad_()
+        yd = fn(xd)
+        yd.backward(torch.from_numpy(dyf).to("cuda:0"))
+        y_ref = fwd(xf)
+        _assert_f32_equal(yd.detach().cpu().numpy(), y_ref, fn.__name__ + " f32")
+        _assert_f32_equal(xd.grad.cpu().numpy(), bwd(dyf, xf if from_input else y_ref), fn.__name__ + " f32 grad")
+
     # two cell steps; the loss sees h of both steps and the final state
     B, H = 5, 24
     gates, c0 = wl.lstm_cell_inputs(2, B, H)
