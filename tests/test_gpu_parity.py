@@ -814,3 +814,17 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
                 res = guard.cpu().numpy().view(np.uint32)
                 _assert_f32_equal(res[16 + o:16 + o + n].view(np.float32), want[a:a + n], what)
             assert np.all(res[:16 + o] == 0x5A5A5A5A) and np.all(res[16 + o + n:] == 0x5A5A5A5A), what
+
+
+# ------------------------------------------------------------------ the C ABI without Python
+def test_native_consumer_of_the_c_abi(gpu):
+    """tests/host_c/gpu_consumer.cpp: hipMalloc'd buffers, a stream of its own, the entry points called
+    from C++, results checked in the same program against the CPU checker."""
+    import os
+    import subprocess
+    import __graft_entry__ as entry
+    exe = entry.NATIVE_CONSUMER
+    assert os.path.exists(exe), f"{exe} is not built; run __graft_entry__.build()"
+    res = subprocess.run([exe], capture_output=True, text=True, timeout=150)
+    assert res.returncode == 0, res.stdout + res.stderr
+    assert res.stdout.strip().endswith("all match"), res.stdout
