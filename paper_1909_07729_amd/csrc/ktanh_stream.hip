@@ -9,6 +9,8 @@ using namespace ktanh_device;
 
 namespace {
 
+static_assert(kBlock == 64, "the loose elements (fewer than 64) are taken by the one wavefront of block 0");
+
 // ---------------------------------------------------------------------------------------------
 // Element-wise streaming kernel over `nvec` 128-bit vectors plus up to `n_edge` loose elements.
 //   vin, vout : 16-byte aligned body (nvec vectors)
@@ -30,33 +32,28 @@ __device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
     else return apply_vec_bf16<OP, WIDE>(v, tab);
 }
 
-template <bool F32, int OP, bool WIDE, int kUnroll>
+template <bool F32, int OP, bool WIDE>
 __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *vin, uint4 *vout,  // may be equal
                                                         unsigned long long nvec, EdgeArgs edge,
                                                         KtLutPack pack)
 {
     const LaneTable tab(pack);
 
-    // One tile of kBlock * kUnroll vectors per block, no loop: fresh blocks keep loads and stores
-    // of different tiles overlapped, which a grid-stride loop over the same tiles does not (measured:
-    // 6.5 against 6.0 TB/s on a 537 MB stream).  Single-wavefront blocks with one vector per lane
-    // measured best for every operation (5 % over 256-thread blocks on a 105 MB tensor): with 32
-    // independent wavefronts per compute unit even GELU's arithmetic hides under the stream.
-    const unsigned long long at = (unsigned long long)blockIdx.x * (kBlock * kUnroll) + threadIdx.x;
-    uint4 v[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-        v[u] = uint4{0u, 0u, 0u, 0u};
-        if (at + (unsigned long long)u * kBlock < nvec) v[u] = load_stream(vin + at + u * kBlock);
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) v[u] = apply_vec<F32, OP, WIDE>(v[u], tab);
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-        if (at + (unsigned long long)u * kBlock < nvec) store_stream(vout + at + u * kBlock, v[u]);
+    // One vector per lane, one tile of kBlock vectors per block, no loop: fresh blocks keep loads and
+    // stores of different tiles overlapped, which a grid-stride loop over the same tiles does not
+    // (measured: 6.5 against 6.0 TB/s on a 537 MB stream).  Single-wavefront blocks measured best for
+    // every operation (5 % over 256-thread blocks on a 105 MB tensor, two vectors per lane another
+    // 3-5 % slower): with 32 independent wavefronts per compute unit even GELU's arithmetic hides
+    // under the stream.
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const bool live_vec = at < nvec;
+    uint4 v = uint4{0u, 0u, 0u, 0u};
+    if (live_vec) v = load_stream(vin + at);
+    v = apply_vec<F32, OP, WIDE>(v, tab);
+    if (live_vec) store_stream(vout + at, v);
 
     // Loose elements before and after the aligned body: first wavefront of block 0.
-    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+    if (edge.n_edge != 0 && blockIdx.x == 0) {  // uniform over the block
         const unsigned k = threadIdx.x;
         const bool live = k < edge.n_edge;
         const unsigned long long i =
@@ -125,7 +122,7 @@ __global__ __launch_bounds__(kBlock) void narrow_stream_kernel(const uint4 *__re
     const uint2 o = narrow_ktanh_vec(v, tab);
     if (at < nvec) store_stream(vout + at, o);
 
-    if (edge.n_edge != 0 && blockIdx.x == 0 && threadIdx.x < 64) {
+    if (edge.n_edge != 0 && blockIdx.x == 0) {  // uniform over the block
         const unsigned k = threadIdx.x;
         const bool live = k < edge.n_edge;
         const unsigned long long i = k < edge.n_head ? k : edge.n_total - edge.n_edge + k;
@@ -214,11 +211,10 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
         edge.n_edge = (unsigned)(head + tail);
         const uint4 *vin = reinterpret_cast<const uint4 *>(static_cast<const char *>(in) + head * kElem);
         uint4 *vout = reinterpret_cast<uint4 *>(static_cast<char *>(out) + head * kElem);
-        constexpr int kUnroll = 1;
-        size_t tiles = (nvec + (size_t)kBlock * kUnroll - 1) / ((size_t)kBlock * kUnroll);
+        size_t tiles = (nvec + kBlock - 1) / kBlock;
         if (tiles == 0) tiles = 1;  // edges only
         if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        return launch_checked(stream_kernel<F32, OP, WIDE, kUnroll>, (unsigned)tiles, kBlock, stream,
+        return launch_checked(stream_kernel<F32, OP, WIDE>, (unsigned)tiles, kBlock, stream,
                               vin, vout, (unsigned long long)nvec, edge, pack);
     }
     const size_t want = (n + kBlock - 1) / kBlock;
