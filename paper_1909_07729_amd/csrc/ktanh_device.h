@@ -71,7 +71,9 @@ struct LaneTable {
 //                 and (|x| >> r) = (E_i << (7 - r)) + (M_i >> r) exactly for r <= 7, so the slot
 //                 stores base_t = (E_t << 7) + b_t - (E_i << (7 - r_t)) and the magnitude is
 //                 shifted whole: no mantissa mask.  (The saturation slot shifts by 15: 0 is left.)
-//     |x| < T1  = input passed through.
+//     |x| < T1  = one more slot as well: the slot index is taken from max(|x|, 0x3E70), which sends
+//                 every magnitude below T1 = 0x3E80 to slot 39 (the index of 0x3E7x), and that slot
+//                 holds base 0, shift 0, so the magnitude comes out as it went in.
 //   64 intervals (WIDE = true): index = 2 low exponent bits, 4 high mantissa bits; all 64 lanes hold
 //     table entries, so saturation is a select of its own.
 struct SlotPair {
@@ -89,8 +91,9 @@ __device__ __forceinline__ SlotPair fetch_slots(uint32_t mag2, const LaneTable &
         sp.e_hi = tab.get(mag2 >> 17);  // same bits of the high value
     } else {
         sp.key2 = as_u32(__builtin_elementwise_min(as_u16x2(mag2), splat(0x4080)));
-        sp.e_lo = tab.get(sp.key2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
-        sp.e_hi = tab.get(sp.key2 >> 18);  // same bits of the high value
+        const uint32_t idx2 = as_u32(__builtin_elementwise_max(as_u16x2(sp.key2), splat(0x3E70)));
+        sp.e_lo = tab.get(idx2 >> 2);   // bits [7:2] <- bits [9:4] of the low value
+        sp.e_hi = tab.get(idx2 >> 18);  // same bits of the high value
     }
     return sp;
 }
@@ -101,10 +104,10 @@ __device__ __forceinline__ uint32_t finish_mag_pair(uint32_t mag2, const SlotPai
     const uint32_t base2 = __builtin_amdgcn_perm(sp.e_hi, sp.e_lo, 0x07060302u);
     const uint32_t r2 = __builtin_amdgcn_perm(sp.e_hi, sp.e_lo, 0x05040100u);
     const uint32_t lut2 = as_u32(as_u16x2(base2) + (as_u16x2(sp.key2) >> as_u16x2(r2)));
+    if constexpr (!WIDE) return lut2;  // pass-through and saturation are table slots
     // 0xFFFF in each half whose magnitude is below T1 = 0.25 (0x3E80): sign of a 16-bit difference
     const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
     const uint32_t res = bitsel(pass, mag2, lut2);
-    if constexpr (!WIDE) return res;
     const uint32_t beyond = sign_mask_pair(as_u32(as_i16x2(0x407F407Fu) - as_i16x2(mag2)));
     return bitsel(beyond, 0x3F803F80u, res);
 }
@@ -133,10 +136,10 @@ __device__ __forceinline__ uint32_t ktanh_pair(uint32_t w, const LaneTable &tab)
     return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
 }
 
-// True in a lane where any of the given BFloat16 magnitude pairs holds a NaN.
-__device__ __forceinline__ bool any_nan_pair(uint32_t mag2)
+// Non-zero where either BFloat16 magnitude of the pair is a NaN (> 0x7F80).
+__device__ __forceinline__ uint32_t nan_bits_pair(uint32_t mag2)
 {
-    return as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x7F80))) != 0u;
+    return as_u32(__builtin_elementwise_sub_sat(as_u16x2(mag2), splat(0x7F80)));
 }
 __device__ __forceinline__ uint32_t max_pair(uint32_t a2, uint32_t b2)
 {

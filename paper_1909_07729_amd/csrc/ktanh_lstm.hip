@@ -47,9 +47,10 @@ __device__ __forceinline__ GateWords load_gates(const uint32_t *step_base, GateO
     return q;
 }
 
-__device__ __forceinline__ bool not_finite(float x)
+// Non-zero where x is an infinity or a NaN.
+__device__ __forceinline__ uint32_t not_finite(float x)
 {
-    return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u;
+    return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u ? 1u : 0u;
 }
 
 // One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
@@ -80,16 +81,18 @@ __device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, f
 // lane needs them (a wavefront-uniform branch, so that the cross-lane table reads still run with
 // every lane enabled).  always_checked: the caller's table lets |K| exceed 1, so the state may
 // overflow on the way.
+// `suspect` is a per-lane flag word (non-zero = this lane's state may not be finite), kept as a
+// number so that it joins the gate test with one OR.
 template <bool WIDE>
-__device__ __forceinline__ uint32_t guarded_step(const GateWords &q, float2 &c, bool &suspect,
-                                                 bool always_checked, const LaneTable &tab)
+__device__ __forceinline__ uint32_t guarded_step(const GateWords &q, float2 &c, uint32_t &suspect,
+                                                 uint32_t always_checked, const LaneTable &tab)
 {
     const uint32_t worst = max_pair(max_pair(q.i & kMag2, q.f & kMag2),
                                     max_pair(q.g & kMag2, q.o & kMag2));
     uint32_t h;
-    if (__builtin_amdgcn_ballot_w64(suspect || any_nan_pair(worst)) != 0) {
+    if (__builtin_amdgcn_ballot_w64((nan_bits_pair(worst) | suspect) != 0u) != 0) {
         h = lstm_step<true, WIDE>(q, c.x, c.y, tab);
-        suspect = always_checked || not_finite(c.x) || not_finite(c.y);
+        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
     } else {
         h = lstm_step<false, WIDE>(q, c.x, c.y, tab);
     }
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
                                                            const float2 *c_in, float2 *c_out,  // may be equal
                                                            uint32_t *__restrict__ h_out, unsigned T,
                                                            unsigned n_pairs, unsigned H2,
-                                                           bool always_checked, KtLutPack pack)
+                                                           unsigned always_checked, KtLutPack pack)
 {
     const LaneTable tab(pack);
     const unsigned p = blockIdx.x * kCellBlock + threadIdx.x;
@@ -125,12 +128,12 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
     const uint32_t *ahead = gates;  // the next step to fetch
     uint32_t *h_row = h_out;        // the next step to store
     unsigned t = 0;
-    bool suspect;
+    uint32_t suspect;
 
     if (T >= 2u * kStages) {
 #pragma unroll
         for (int s = 0; s < kStages; ++s, ahead += row_step) stage[s] = load_gates(ahead, at);
-        suspect = always_checked || not_finite(c.x) || not_finite(c.y);
+        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
         // Steady state: each stage is refilled right after the step that consumed it, in place
         // (the refill follows the step's last use of the old words, so that no register copies --
         // which would have to wait for every load in flight -- are needed at the end of the body).
@@ -153,7 +156,7 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
                 ahead += row_step;
             }
         }
-        suspect = always_checked || not_finite(c.x) || not_finite(c.y);
+        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
     }
 
     // The last steps (fewer than 2 * kStages): stage[0] is the current one, the ring moves up.
@@ -209,7 +212,7 @@ ktanh_status_t launch_cell(const uint16_t *gates, const float *c_in, float *c_ou
                           reinterpret_cast<const uint32_t *>(gates),
                           reinterpret_cast<const float2 *>(c_in), reinterpret_cast<float2 *>(c_out),
                           reinterpret_cast<uint32_t *>(h_out), (unsigned)T, (unsigned)n_pairs,
-                          (unsigned)(H / 2), !within_unit, pack);
+                          (unsigned)(H / 2), within_unit ? 0u : 1u, pack);
 }
 
 }  // namespace

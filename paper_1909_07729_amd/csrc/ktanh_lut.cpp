@@ -75,6 +75,9 @@ ktanh_status_t pack_slots(const ktanh_lut_t *lut, KtLutPack *pack, bool fold_inp
         if (fold_input_exponent) base -= (string >> 3) << (7 - r);  // string >> 3 = input exponent
         pack->slot[string & 63] = ((uint32_t)(base & 0xFFFF) << 16) | (uint32_t)r;
     }
+    // string 999 (magnitudes 0x3E70..0x3E7F, where the BFloat16 kernels send everything below T1):
+    // base 0, shift 0 returns the magnitude itself
+    if (fold_input_exponent) pack->slot[999 & 63] = 0u;
     return KT_OK;
 }
 
