@@ -10,15 +10,17 @@
  *     travels to the GPU inside the kernel arguments.  NULL selects the paper's Table 1.
  *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.  Calls only enqueue
  *     work: they return without synchronising and may be issued from several host threads.  The
- *     library keeps nothing between calls except two values computed once per process (the
- *     device's compute-unit count and the fitted 64-interval table).
+ *     library keeps nothing between calls except the fitted 64-interval table, computed once per
+ *     process on first use.
  *   - BFloat16 tensors are arrays of uint16_t bit patterns (s:1, E:8, M:7); Float32 tensors of
  *     K-TanH are arrays of uint32_t bit patterns (s:1, E:8, M:23).  Tensors are dense and 1-D as
  *     far as the library is concerned (any contiguous shape works).
  *   - `out == in` (and `c_out == c_in`) is allowed; any other overlap is undefined.
- *   - Pointers must be aligned to their element size (else KT_ERR_ALIGN).  When `in` and `out`
- *     are congruent modulo 16 bytes the body runs on 128-bit accesses and the ragged ends are
- *     peeled; otherwise a slower element-wise kernel is used.  Results are identical.
+ *   - Pointers must be aligned to their element size (else KT_ERR_ALIGN); nothing more is
+ *     required.  The body always runs on 128-bit accesses: the elements before the output's first
+ *     16-byte boundary and after its last are peeled, and an input that is not congruent to the
+ *     output modulo 16 bytes is read with unaligned 128-bit loads (measured within a few per cent
+ *     of the aligned case).  Results are identical.
  *   - n == 0 (or T, B or H == 0) returns KT_OK without launching anything.
  *   - Errors are returned, never thrown; nothing is launched when an argument is rejected.  A
  *     failed launch is reported as KT_ERR_HIP.
@@ -152,7 +154,7 @@ ktanh_status_t klstm_cell64(const uint16_t *gates, const float *c_in, float *c_o
  *   ksigmoid_f32(x) = 0.5 * Kf(0.5 x) + 0.5
  *   kswish_f32(x)   = x * (0.5 * Kf(0.5 x) + 0.5)
  *   kgelu_f32(x)    = (0.5 x) * (1 + Kf(c * (x + a * ((x*x)*x))))
- * in, out: device, n elements each, 4-byte aligned (16-byte congruent pointers take the vector path).
+ * in, out: device, n elements each, 4-byte aligned.
  * NaN in gives NaN out. */
 ktanh_status_t ksigmoid_f32(const float *in, float *out, size_t n, const ktanh_lut_t *lut,
                             ktanh_stream_t stream);
@@ -171,9 +173,9 @@ ktanh_status_t kgelu64_f32(const float *in, float *out, size_t n, const ktanh_lu
 /* K-TanH on BFloat16 inputs that arrive as Float32: each value is rounded to BFloat16 (nearest even)
  * and goes through ktanh_bf16 -- the conversion Section 2.5 leaves out of the paper's cycle count,
  * fused into the load (6 bytes of traffic per element instead of 4 + 4 + 4).
- * in: device, n Float32, 4-byte aligned; out: device, n BFloat16, 2-byte aligned.  The vector path
- * needs `in` 16-byte and `out` 8-byte aligned after the same number of peeled elements; other
- * alignments take an element-wise kernel.  NaN in gives NaN out (which NaN is unspecified). */
+ * in: device, n Float32, 4-byte aligned; out: device, n BFloat16, 2-byte aligned (any such pair:
+ * the body reads 128 bits and writes 64 bits per lane from wherever `out` reaches an 8-byte boundary).
+ * NaN in gives NaN out (which NaN is unspecified). */
 ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
                                  ktanh_stream_t stream);
 
@@ -219,9 +221,8 @@ ktanh_status_t kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *
 ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
                               const ktanh_lut_t *lut, ktanh_stream_t stream);
 
-/* The same four gradients on Float32 tensors (n elements each, device, 4-byte aligned; pointers
- * that are all 16-byte aligned take the vector path): the formulas above with nothing rounded to
- * BFloat16 and, inside Swish and GELU, the Float32 K-TanH of ksigmoid_f32 / kgelu_f32.
+/* The same four gradients on Float32 tensors (n elements each, device, 4-byte aligned): the
+ * formulas above with nothing rounded to BFloat16 and, inside Swish and GELU, the Float32 K-TanH of ksigmoid_f32 / kgelu_f32.
  * y, s: forward outputs of ktanh_f32 / ksigmoid_f32 as Float32 values; x: forward input.
  * dx may alias dy or the other input. */
 ktanh_status_t ktanh_f32_backward(const float *dy, const float *y, float *dx, size_t n,

@@ -94,49 +94,49 @@ __device__ __forceinline__ uint32_t grad_word(uint32_t dy_w, uint32_t v_w, const
 }
 
 // Two input streams, one output stream (which may be one of the inputs): 6 bytes per BFloat16
-// element, 12 per Float32 element.  One wavefront per block, one 128-bit vector per lane and stream;
-// the whole last block also takes the loose elements behind the last full vector.  The table reads
-// of Swish and GELU need every lane enabled, so bounds predicate only the loads and stores.
-template <class ELEM, int GRAD>
-__global__ __launch_bounds__(kBlock) void grad_stream_kernel(const uint4 *vdy, const uint4 *vv,
-                                                             uint4 *vdx, unsigned long long nvec,
-                                                             const ELEM *dy, const ELEM *v, ELEM *dx,
-                                                             unsigned long long n, KtLutPack pack)
+// element, 12 per Float32 element.  One wavefront per block, one 128-bit vector per lane and stream.
+// The body starts where `dx` reaches a 16-byte boundary and its tiles are cut at 1 KiB boundaries of
+// `dx` (skew = index of the first vector inside its 1 KiB group); the elements before and after the
+// body (n_edge < 64 of them) are taken by block 0.  IN_UNALIGNED: an input disagrees with `dx`
+// modulo 16 bytes, so both are read with 16-byte loads from element-aligned addresses.  The table
+// reads of Swish and GELU need every lane enabled, so bounds predicate only the loads and stores.
+template <class ELEM>
+struct GradArgs {
+    const ELEM *dy, *v;  // the whole tensors
+    ELEM *dx;
+    unsigned long long n, nvec;
+    unsigned n_head, n_edge, skew;
+};
+
+template <class ELEM, int GRAD, bool IN_UNALIGNED>
+__global__ __launch_bounds__(kBlock) void grad_stream_kernel(GradArgs<ELEM> g, KtLutPack pack)
 {
-    constexpr unsigned kPerVec = 16 / sizeof(ELEM);
     const LaneTable tab(pack);
-    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
-    const bool live = at < nvec;
+    const unsigned long long slot = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned long long at = slot - g.skew;
+    const bool live = slot >= g.skew && at < g.nvec;
+    const char *bdy = reinterpret_cast<const char *>(g.dy + g.n_head) + 16 * at;
+    const char *bv = reinterpret_cast<const char *>(g.v + g.n_head) + 16 * at;
     uint4 a = uint4{0u, 0u, 0u, 0u}, b = uint4{0u, 0u, 0u, 0u};
     if (live) {
-        a = load_stream(vdy + at);
-        b = load_stream(vv + at);
+        if constexpr (IN_UNALIGNED) {
+            a = load_stream_unaligned(bdy);
+            b = load_stream_unaligned(bv);
+        } else {
+            a = load_stream(reinterpret_cast<const uint4 *>(bdy));
+            b = load_stream(reinterpret_cast<const uint4 *>(bv));
+        }
     }
     const uint4 r = uint4{grad_word<ELEM, GRAD>(a.x, b.x, tab), grad_word<ELEM, GRAD>(a.y, b.y, tab),
                           grad_word<ELEM, GRAD>(a.z, b.z, tab), grad_word<ELEM, GRAD>(a.w, b.w, tab)};
-    if (live) store_stream(vdx + at, r);
-    if (blockIdx.x == gridDim.x - 1) {  // uniform over the block
-        const unsigned long long loose = nvec * kPerVec + threadIdx.x;
-        const bool some = loose < n;
-        const uint32_t d1 = some ? dy[loose] : 0u, v1 = some ? v[loose] : 0u;
+    if (live) store_stream(reinterpret_cast<uint4 *>(g.dx + g.n_head) + at, r);
+    if (g.n_edge != 0 && blockIdx.x == 0) {  // uniform over the block
+        const unsigned k = threadIdx.x;
+        const bool some = k < g.n_edge;
+        const unsigned long long i = k < g.n_head ? k : g.n - g.n_edge + k;
+        const uint32_t d1 = some ? g.dy[i] : 0u, v1 = some ? g.v[i] : 0u;
         const uint32_t r1 = grad_word<ELEM, GRAD>(d1, v1, tab);
-        if (some) dx[loose] = (ELEM)r1;
-    }
-}
-
-// Any alignment: one element per lane and pass; the trip count is the same for the whole block.
-template <class ELEM, int GRAD>
-__global__ __launch_bounds__(kBlock) void grad_element_kernel(const ELEM *dy, const ELEM *v, ELEM *dx,
-                                                              unsigned long long n, KtLutPack pack)
-{
-    const LaneTable tab(pack);
-    const unsigned long long stride = (unsigned long long)gridDim.x * kBlock;
-    for (unsigned long long base = (unsigned long long)blockIdx.x * kBlock; base < n; base += stride) {
-        const unsigned long long i = base + threadIdx.x;
-        const bool some = i < n;
-        const uint32_t d1 = some ? dy[i] : 0u, v1 = some ? v[i] : 0u;
-        const uint32_t r1 = grad_word<ELEM, GRAD>(d1, v1, tab);
-        if (some) dx[i] = (ELEM)r1;
+        if (some) g.dx[i] = (ELEM)r1;
     }
 }
 
@@ -148,28 +148,30 @@ ktanh_status_t launch_grad(const void *dy, const void *v, void *dx, size_t n, co
     constexpr size_t kPerVec = 16 / sizeof(ELEM);
     if (n == 0) return KT_OK;
     if (dy == nullptr || v == nullptr || dx == nullptr) return KT_ERR_NULL;
-    const uintptr_t all = reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(v) |
-                          reinterpret_cast<uintptr_t>(dx);
-    if (all & (sizeof(ELEM) - 1)) return KT_ERR_ALIGN;
+    const uintptr_t ady = reinterpret_cast<uintptr_t>(dy), av = reinterpret_cast<uintptr_t>(v),
+                    adx = reinterpret_cast<uintptr_t>(dx);
+    if ((ady | av | adx) & (sizeof(ELEM) - 1)) return KT_ERR_ALIGN;
     if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
     KtLutPack pack;
     const ktanh_status_t st = sizeof(ELEM) == 2 ? kt_pack_lut_bf16(lut, &pack) : kt_pack_lut_f32(lut, &pack);
     if (st != KT_OK) return st;
-    const ELEM *edy = static_cast<const ELEM *>(dy), *ev = static_cast<const ELEM *>(v);
-    ELEM *edx = static_cast<ELEM *>(dx);
-    if ((all & 15) == 0) {
-        const size_t nvec = n / kPerVec;
-        size_t tiles = (nvec + kBlock - 1) / kBlock;
-        if (tiles == 0) tiles = 1;  // loose elements only
-        if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
-        return launch_checked(grad_stream_kernel<ELEM, GRAD>, (unsigned)tiles, kBlock, stream,
-                              static_cast<const uint4 *>(dy), static_cast<const uint4 *>(v),
-                              static_cast<uint4 *>(dx), (unsigned long long)nvec, edy, ev, edx,
-                              (unsigned long long)n, pack);
-    }
-    const size_t want = (n + kBlock - 1) / kBlock;
-    return launch_checked(grad_element_kernel<ELEM, GRAD>, (unsigned)(want < 8192 ? want : 8192),
-                          kBlock, stream, edy, ev, edx, (unsigned long long)n, pack);
+    GradArgs<ELEM> g;
+    g.dy = static_cast<const ELEM *>(dy);
+    g.v = static_cast<const ELEM *>(v);
+    g.dx = static_cast<ELEM *>(dx);
+    g.n = n;
+    size_t head = ((16 - (adx & 15)) & 15) / sizeof(ELEM);
+    if (head > n) head = n;
+    g.nvec = (n - head) / kPerVec;
+    g.n_head = (unsigned)head;
+    g.n_edge = (unsigned)(n - g.nvec * kPerVec);
+    g.skew = (unsigned)((reinterpret_cast<uintptr_t>(g.dx + head) / 16) % kBlock);
+    size_t tiles = (g.nvec + g.skew + kBlock - 1) / kBlock;
+    if (tiles == 0) tiles = 1;  // edge elements only
+    if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+    if ((ady & 15) == (adx & 15) && (av & 15) == (adx & 15))
+        return launch_checked(grad_stream_kernel<ELEM, GRAD, false>, (unsigned)tiles, kBlock, stream, g, pack);
+    return launch_checked(grad_stream_kernel<ELEM, GRAD, true>, (unsigned)tiles, kBlock, stream, g, pack);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -217,6 +217,14 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p)
     const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
     return uint4{t.x, t.y, t.z, t.w};
 }
+// The same 16 bytes from an address that is only aligned to its elements (the target allows
+// unaligned vector loads; the copy lets the compiler pick a legal access).
+__device__ __forceinline__ uint4 load_stream_unaligned(const void *p)
+{
+    u32x4 t;
+    __builtin_memcpy(&t, p, sizeof t);
+    return uint4{t.x, t.y, t.z, t.w};
+}
 __device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
 {
     const u32x4 t = {v.x, v.y, v.z, v.w};
