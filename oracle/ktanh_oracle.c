@@ -10,7 +10,9 @@
  * What each function follows (arXiv:1909.07729):
  *   oracle_table1          Table 1 (optimised parameters for BFloat16 inputs)
  *   oracle_fit_lut_bmin0   the ablation of Section 3: the fit with b_min = 0
- *                          (no table printed; pinned by exhaustive search)
+ *                          (no table printed; pinned by exhaustive search and
+ *                          by Table 2, whose two error figures for K-TanH are
+ *                          this table's to the printed digits)
  *   oracle_fit_lut         Section 2.4, Steps 1-3, eq. (1) and the b_min/b_max
  *                          bounds (eq. (2))
  *   oracle_ktanh_bf16/f32  Algorithm 1; thresholds T1, T2 and the interval

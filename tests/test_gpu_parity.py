@@ -816,6 +816,29 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             assert np.all(res[:16 + o] == 0x5A5A5A5A) and np.all(res[16 + o + n:] == 0x5A5A5A5A), what
 
 
+# ------------------------------------------------------------------ the accuracy report
+def test_accuracy_report_figures_equal_the_oracle_s(gpu, oracle):
+    """paper_1909_07729_amd.report measures the three tables with the GPU kernels; the error figures
+    it prints must be the ones the oracle gives for the same tables."""
+    from paper_1909_07729_amd import report
+    bits = wl.all_bf16_patterns()
+    bits = bits[(bits & 0x7FFF) < 0x7F80]
+    x = wl.bf16_bits_to_f32(bits).astype(np.float64)
+    want = [oracle.ktanh_bf16(bits), oracle.ktanh64_bf16(bits), oracle.ktanh_bf16(bits, oracle.fit_lut_bmin0())]
+    rows = report.error_rows()
+    assert len(rows) == 3
+    for row, y in zip(rows, want):
+        err = np.abs(wl.bf16_bits_to_f32(y).astype(np.float64) - np.tanh(x))
+        assert row["max_abs"] == float(err.max()), row["table"]
+        assert row["at"] == f"0x{int(bits[int(np.argmax(err))]):04X}"
+        assert row["elements_per_s"] > 1e11
+    assert rows[0]["max_abs"] < rows[1]["max_abs"] < rows[2]["max_abs"]
+    assert rows[1]["mean_abs_region"] < rows[0]["mean_abs_region"] < rows[2]["mean_abs_region"]
+    derived = report.derived_rows()
+    assert [r["op"] for r in derived] == ["Sigmoid", "Swish", "GELU (tanh form)"]
+    assert all(r["mean_abs_64"] < r["mean_abs_32"] for r in derived)
+
+
 # ------------------------------------------------------------------ the C ABI without Python
 def test_native_consumer_of_the_c_abi(gpu):
     """tests/host_c/gpu_consumer.cpp: hipMalloc'd buffers, a stream of its own, the entry points called
