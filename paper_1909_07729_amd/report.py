@@ -7,8 +7,8 @@ For each table (Table 1, the 64-interval fit, the ablation's b_min = 0 fit) ever
 input goes through the GPU kernel and the result is compared with TanH in double precision; the
 derived Sigmoid, Swish and GELU are compared with their exact forms on |x| <= 16.  Throughput is
 taken on a [50, 128, 4096] BFloat16 tensor.  (The ablation's row shows the two error figures that
-Table 2 of the paper prints for K-TanH, 1.67e-2 and 3.03 %.)  The reference values are numpy's, computed here; the
-library's arithmetic is not repeated on the CPU.
+Table 2 of the paper prints for K-TanH, 1.67e-2 and 3.03 %.)  The reference values are numpy's,
+computed here; the library's arithmetic is not repeated on the CPU.
 """
 from __future__ import annotations
 
