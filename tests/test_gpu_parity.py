@@ -285,6 +285,49 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
         assert np.array_equal(_to_host(hd, np.uint16), want_h), f"replay {replay}"
 
 
+def test_graph_replay_of_the_later_entry_points(gpu, oracle):
+    """64-interval, Float32-tensor, fused-conversion and gradient calls (aligned and unaligned
+    inputs) recorded into one HIP graph and replayed three times with eager work in between."""
+    binding, torch = gpu
+    x = wl.mlp_preactivations(40009, seed=70)
+    dy = wl.f32_to_bf16_bits(np.random.Generator(np.random.PCG64(71)).standard_normal(x.size, dtype=np.float32))
+    xf = wl.f32_mixture(40009, seed=72).view(np.float32)
+    xd, dyd = _to_dev(torch, x), _to_dev(torch, dy)
+    xfd = torch.from_numpy(xf).to("cuda:0")
+    n = x.size - 5
+    outs = {k: torch.empty_like(xd) for k in ("t64", "gb", "gb_unaligned")}
+    outs["sf"] = torch.empty_like(xfd)
+    outs["nb"] = torch.empty(xf.size, dtype=torch.int16, device="cuda:0")
+    outs["gf"] = torch.empty_like(xfd)
+    binding.ktanh64_bf16(xd, out=outs["t64"])                         # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.ktanh64_bf16(xd, out=outs["t64"])
+        binding.kgelu_backward(dyd, xd, dx=outs["gb"])
+        binding.kgelu_backward(dyd[3:3 + n], xd[2:2 + n], dx=outs["gb_unaligned"][:n])
+        binding.kswish64_f32(xfd, out=outs["sf"])
+        binding.ktanh_f32_to_bf16(xfd, out=outs["nb"])
+        binding.kswish_f32_backward(xfd, xfd, dx=outs["gf"])
+    with np.errstate(all="ignore"):
+        want = {"t64": oracle.ktanh64_bf16(x), "gb": oracle.kgelu_backward(dy, x),
+                "gb_unaligned": oracle.kgelu_backward(dy[3:3 + n], x[2:2 + n]),
+                "sf": oracle.kswish64_f32(xf), "nb": oracle.ktanh_f32_to_bf16(xf),
+                "gf": oracle.kswish_f32_backward(xf, xf)}
+    for replay in range(3):
+        for t in outs.values():
+            t.zero_()                                                 # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(_to_host(outs["t64"], np.uint16), want["t64"]), f"replay {replay}"
+        _assert_bf16_equal(_to_host(outs["gb"], np.uint16), want["gb"], False, f"kgelu_backward replay {replay}")
+        _assert_bf16_equal(_to_host(outs["gb_unaligned"], np.uint16)[:n], want["gb_unaligned"], False, f"unaligned replay {replay}")
+        _assert_f32_equal(outs["sf"].cpu().numpy(), want["sf"], f"kswish64_f32 replay {replay}")
+        _assert_bf16_equal(_to_host(outs["nb"], np.uint16), want["nb"], False, f"ktanh_f32_to_bf16 replay {replay}")
+        _assert_f32_equal(outs["gf"].cpu().numpy(), want["gf"], f"kswish_f32_backward replay {replay}")
+
+
 # ------------------------------------------------------------------ 64-interval variant
 def test_ktanh64_exhaustive_ragged_and_custom_table(gpu, oracle):
     binding, torch = gpu
