@@ -189,6 +189,8 @@ def run_extras(torch, binding, wl, upload, xs, ys):
     # yardstick: the runtime's own device-to-device copy of the same tensor (same bytes, no arithmetic)
     record("plain_copy_same_size", "hipMemcpyAsync device-to-device of the headline tensor, same 8 rotating pairs",
            lambda i: ys[i % ROTATE].copy_(xs[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
+    record("stream_copy_same_shape", "the same launch shape and access policies with no arithmetic (ktanh_stream_copy), same 8 rotating pairs",
+           lambda i: binding.ktanh_stream_copy(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
     record("ktanh64_bf16", "[50,128,4096] bf16 as in the headline, 64-interval table, 8 rotating buffer pairs",
            lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), xs[0].numel(), 4, 2000, 500)
 
@@ -272,6 +274,8 @@ def run_probe(torch, binding, wl, upload, headline, x):
     of known size (the yardstick the HBM counters are scaled by)."""
     for i in range(ROTATE):
         headline(i)
+    for i in range(ROTATE):
+        binding.ktanh_stream_copy(headline.inputs[i], out=headline.outputs[i])
     for i in range(ROTATE):
         binding.ktanh64_bf16(headline.inputs[i], out=headline.outputs[i])
     for i in range(ROTATE):

@@ -102,6 +102,13 @@ ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n, const ktanh_l
 ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
                      ktanh_stream_t stream);
 
+/* Not an operation of the paper: copies n 16-bit elements with exactly the accesses of ktanh_bf16
+ * (same launch shape, same load and store policies) and no arithmetic.  It is the yardstick the
+ * benchmark reports next to the K-TanH figures -- what the memory system allows for this launch --
+ * and a device-to-device copy that is faster than the runtime's own on large buffers.
+ * in, out: device, n elements each, 2-byte aligned; out == in allowed. */
+ktanh_status_t ktanh_stream_copy(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
+
 /* ---- 64-interval variant ------------------------------------------------------------------------
  * Section 2.4 (last paragraph): the parameters are 8-bit, so 64 intervals fit where AVX512 held 32
  * 16-bit values.  Index t = (2 LSBs of E_i) << 4 | (4 MSBs of M_i); t = 16..31 covers [0.25, 0.5),

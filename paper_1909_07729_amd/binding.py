@@ -24,7 +24,8 @@ EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "kt
            "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
            "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0",
            "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward")
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
+           "ktanh_stream_copy")
 
 
 class KtanhLut(ctypes.Structure):
@@ -112,10 +113,13 @@ def load_library() -> ctypes.CDLL:
         lib.ktanh_lut64_validate.restype = ctypes.c_int
         for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64",
                      "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward"):
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
+           "ktanh_stream_copy"):
             fn = getattr(lib, name)
             fn.argtypes = [vp, vp, sz, lp64, vp]
             fn.restype = ctypes.c_int
+        lib.ktanh_stream_copy.argtypes = [vp, vp, sz, vp]
+        lib.ktanh_stream_copy.restype = ctypes.c_int
         lib.klstm_cell64.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp64, vp]
         lib.klstm_cell64.restype = ctypes.c_int
         for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
@@ -168,7 +172,8 @@ def ktanh_fit_lut_bmin0() -> KtanhLut:
     if st != 0:
         raise KtanhError(st, "ktanh_fit_lut_bmin0",
            "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward")
+           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
+           "ktanh_stream_copy")
     return lut
 
 
@@ -224,6 +229,20 @@ def _elementwise(name, x, out, lut, stream, dtypes):
 def ktanh_bf16(x, out=None, lut=None, stream=None):
     """K-TanH on a BFloat16 tensor (or its int16/uint16 bit view); ``out`` may be ``x``."""
     return _elementwise("ktanh_bf16", x, out, lut, stream, _BF16_VIEWS)
+
+
+def ktanh_stream_copy(x, out=None, stream=None):
+    """Copies a 16-bit tensor with the accesses of ``ktanh_bf16`` and no arithmetic (the yardstick)."""
+    _check(x, _BF16_VIEWS, "in")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(out, _BF16_VIEWS, "out")
+    if out.numel() != x.numel():
+        raise ValueError("in and out differ in size")
+    st = load_library().ktanh_stream_copy(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_stream_copy")
+    return out
 
 
 def ktanh_f32(x, out=None, lut=None, stream=None):

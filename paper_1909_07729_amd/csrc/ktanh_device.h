@@ -239,13 +239,17 @@ __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offse
                  : "memory");
 }
 
-enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3 };
+// OP_COPY moves the data unchanged: the same accesses with no arithmetic, the yardstick for what the
+// memory system allows in this launch shape.
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_COPY = 4 };
 
 // WIDE selects the 64-interval table layout.
 template <int OP, bool WIDE = false>
 __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
 {
-    if constexpr (OP == OP_TANH) {
+    if constexpr (OP == OP_COPY) {
+        return w;
+    } else if constexpr (OP == OP_TANH) {
         return ktanh_pair<true, WIDE>(w, tab);
     } else if constexpr (OP == OP_SIGMOID) {
         float s_lo, s_hi;

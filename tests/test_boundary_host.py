@@ -192,6 +192,9 @@ def test_gradient_entry_points_reject_bad_arguments(binding):
         assert fn(ctypes.c_void_p(0x1001), fake, fake, 8, None, null) == 2
         assert fn(fake, fake, fake, (1 << 40) + 8, None, null) == 4
         assert fn(fake, fake, fake, 8, ctypes.byref(bad), null) == 3
+    assert lib.ktanh_stream_copy(null, null, 0, null) == 0
+    assert lib.ktanh_stream_copy(fake, null, 8, null) == 1
+    assert lib.ktanh_stream_copy(ctypes.c_void_p(0x1001), fake, 8, null) == 2
     for name in ("ktanh_f32_backward", "ksigmoid_f32_backward"):
         fn = getattr(lib, name)
         assert fn(null, null, null, 0, null) == 0

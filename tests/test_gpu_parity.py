@@ -285,6 +285,23 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
         assert np.array_equal(_to_host(hd, np.uint16), want_h), f"replay {replay}"
 
 
+def test_stream_copy_is_the_identity(gpu):
+    """ktanh_stream_copy moves bits unchanged (NaN payloads included), for any alignment, in place too."""
+    binding, torch = gpu
+    x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(100003, seed=73)])
+    xd = _to_dev(torch, x)
+    assert np.array_equal(_to_host(binding.ktanh_stream_copy(xd), np.uint16), x)
+    n = x.size - 16
+    for off_in, off_out in ((0, 0), (1, 1), (3, 0), (0, 5), (7, 2)):
+        outd = torch.full((x.size + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        binding.ktanh_stream_copy(xd[off_in:off_in + n], out=outd[8 + off_out:8 + off_out + n])
+        res = _to_host(outd, np.uint16)
+        assert np.array_equal(res[8 + off_out:8 + off_out + n], x[off_in:off_in + n]), (off_in, off_out)
+        assert np.all(res[:8 + off_out] == 0x5A5A) and np.all(res[8 + off_out + n:] == 0x5A5A)
+    binding.ktanh_stream_copy(xd, out=xd)
+    assert np.array_equal(_to_host(xd, np.uint16), x)
+
+
 def test_graph_replay_of_the_later_entry_points(gpu, oracle):
     """64-interval, Float32-tensor, fused-conversion and gradient calls (aligned and unaligned
     inputs) recorded into one HIP graph and replayed three times with eager work in between."""
@@ -795,6 +812,7 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
     with np.errstate(all="ignore"):
         yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
         cases = {
+            "ktanh_stream_copy": ("bf16", xb),
             "ktanh_bf16": ("bf16", yb), "ksigmoid": ("bf16", sb), "kswish": ("bf16", oracle.kswish(xb)),
             "kgelu": ("bf16", oracle.kgelu(xb)), "ktanh64_bf16": ("bf16", oracle.ktanh64_bf16(xb)),
             "ksigmoid64": ("bf16", oracle.ksigmoid64(xb)), "kswish64": ("bf16", oracle.kswish64(xb)),
