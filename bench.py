@@ -165,6 +165,8 @@ def main():
 
     if not args.no_extra:
         result["extra"] = run_extras(torch, binding, wl, upload, xs, ys)
+        # the same launch shape and accesses with no arithmetic, timed in this run: the memory system's ceiling
+        result["roofline"]["copy_same_shape_us"] = result["extra"]["stream_copy_same_shape"]["avg_launch_us"]
     if not args.no_cpu:
         result["cpu_baseline"] = run_cpu_baseline(x_host)
     print(json.dumps(result))
