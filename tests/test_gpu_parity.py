@@ -252,6 +252,31 @@ def test_lstm_cell_full(gpu, oracle):
     _lstm_check(gpu, oracle, gates, c0, per_step=True)
 
 
+def test_lstm_cell_just_below_the_size_limit(gpu, oracle):
+    """B * H / 2 = 2^28 - 16384 cell pairs: the byte offsets inside one time step come within 256 KiB of
+    2^32.  Inputs are drawn on the GPU; the first, middle and last batch rows go through the oracle."""
+    binding, torch = gpu
+    T, B, H = 2, 16383, 32768
+    assert B * H // 2 < (1 << 28) <= (B + 1) * H // 2
+    gen = torch.Generator(device="cuda:0").manual_seed(190908)
+    gates = torch.empty((T, B, 4 * H), dtype=torch.bfloat16, device="cuda:0")
+    for t in range(T):
+        for b0 in range(0, B, 2048):                      # in slabs: the Float32 draw is twice the size
+            rows = min(2048, B - b0)
+            gates[t, b0:b0 + rows] = (torch.randn((rows, 4 * H), generator=gen, device="cuda:0") * 2).to(torch.bfloat16)
+    c0 = torch.randn((B, H), generator=gen, device="cuda:0")
+    c1, h = binding.klstm_cell(gates, c0)
+    rows = [0, 1, B // 2, B - 2, B - 1]
+    g_host = gates[:, rows, :].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    c_ref, h_ref = oracle.klstm_cell(g_host, c0[rows].cpu().numpy())
+    assert np.array_equal(c1[rows].cpu().numpy().view(np.uint32), c_ref.view(np.uint32))
+    assert np.array_equal(h[:, rows, :].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), h_ref)
+    del gates, h
+    with pytest.raises(binding.KtanhError):               # one more row crosses the limit
+        binding.klstm_cell(torch.empty((1, B + 1, 4 * H), dtype=torch.bfloat16, device="cuda:0"),
+                           torch.empty((B + 1, H), device="cuda:0"))
+
+
 def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
     """Every entry point only enqueues kernels, so a stream capture records them; each replay is
     checked against the oracle, with eager work and synchronisation between the replays."""
