@@ -7,7 +7,9 @@
  * parameter table below is typed in from the paper on its own, and every
  * function works on HOST pointers.
  *
- * What each function follows (arXiv:1909.07729):
+ * What each function follows (arXiv:1909.07729); ktanh_bf16_ref, ktanh_f32_ref,
+ * ksigmoid_ref, kswish_ref, kgelu_ref and klstm_cell_ref at the end of the file
+ * are the same six base functions under the GPU library's argument lists:
  *   oracle_table1          Table 1 (optimised parameters for BFloat16 inputs)
  *   oracle_fit_lut_bmin0   the ablation of Section 3: the fit with b_min = 0
  *                          (no table printed; pinned by exhaustive search and
@@ -719,3 +721,64 @@ void oracle_klstm_cell_backward(const uint16_t *gates, const float *c_prev, cons
         }
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* The six base operations once more under the names and argument lists of the
+ * GPU library, with a _ref suffix: host pointers, NULL table = Table 1, the
+ * stream argument ignored, 0 returned.  Thin wrappers over the functions above. */
+static const oracle_lut *table_or_default(const oracle_lut *lut, oracle_lut *storage)
+{
+    if (lut != NULL) return lut;
+    oracle_table1(storage);
+    return storage;
+}
+
+int ktanh_bf16_ref(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_ktanh_bf16(in, out, n, table_or_default(lut, &t1));
+    return 0;
+}
+
+int ktanh_f32_ref(const uint32_t *in, uint32_t *out, size_t n, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_ktanh_f32(in, out, n, table_or_default(lut, &t1));
+    return 0;
+}
+
+int ksigmoid_ref(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_ksigmoid(in, out, n, table_or_default(lut, &t1));
+    return 0;
+}
+
+int kswish_ref(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_kswish(in, out, n, table_or_default(lut, &t1));
+    return 0;
+}
+
+int kgelu_ref(const uint16_t *in, uint16_t *out, size_t n, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_kgelu(in, out, n, table_or_default(lut, &t1));
+    return 0;
+}
+
+int klstm_cell_ref(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out, size_t T,
+                   size_t B, size_t H, const oracle_lut *lut, void *stream)
+{
+    oracle_lut t1;
+    (void)stream;
+    oracle_klstm_cell(gates, c_in, c_out, h_out, T, B, H, table_or_default(lut, &t1));
+    return 0;
+}
+

@@ -754,3 +754,31 @@ def test_f32_backward_functions(oracle):
     assert np.max(np.abs(gl - ge_true)[act]) <= 0.03
     assert np.max(np.abs(oracle.ktanh_f32_backward(ones, y) - (1 - np.tanh(xv) ** 2))) <= 2 * 1.67e-2 + 1e-6
     assert np.max(np.abs(oracle.ksigmoid_f32_backward(ones, s) - s_true * (1 - s_true))) <= 1.67e-2 / 2 + 1e-6
+
+
+def test_ref_named_entry_points_are_the_oracle_functions(oracle):
+    """ktanh_bf16_ref ... klstm_cell_ref: the library's argument lists on host pointers (NULL table =
+    Table 1, stream ignored); they must return what the oracle_* functions return."""
+    import ctypes
+    lib = ctypes.CDLL(oracle.build())
+    x = wl.all_bf16_patterns()
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu"):
+        out = np.empty_like(x)
+        fn = getattr(lib, name + "_ref")
+        fn.restype = ctypes.c_int
+        fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        assert fn(x.ctypes.data, out.ctypes.data, x.size, None, None) == 0
+        assert np.array_equal(out, getattr(oracle, name)(x)), name
+    u = wl.f32_mixture(4099, seed=40)
+    out = np.empty_like(u)
+    lib.ktanh_f32_ref.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    assert lib.ktanh_f32_ref(u.ctypes.data, out.ctypes.data, u.size, None, None) == 0
+    assert np.array_equal(out, oracle.ktanh_f32(u))
+    gates, c0 = wl.lstm_cell_inputs(3, 2, 16)
+    c1, h = np.empty_like(c0), np.empty((3, 2, 16), np.uint16)
+    lib.klstm_cell_ref.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_size_t] * 3 + [ctypes.c_void_p] * 2
+    rows = oracle.table1()
+    assert lib.klstm_cell_ref(gates.ctypes.data, c0.ctypes.data, c1.ctypes.data, h.ctypes.data, 3, 2, 16,
+                              ctypes.byref(rows), None) == 0
+    c_ref, h_ref = oracle.klstm_cell(gates, c0)
+    assert np.array_equal(c1, c_ref) and np.array_equal(h, h_ref)
