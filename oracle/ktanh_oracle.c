@@ -45,7 +45,13 @@
  *                          of the Swish and GELU identities with the K-TanH
  *                          value rebuilt from the input.  Parity unpinned by
  *                          the paper; pinned by double re-evaluation, by the
- *                          distance to the exact derivatives, and by hand
+ *                          distance to the exact derivatives, and by hand.
+ *                          oracle_kswish64_backward, oracle_kgelu64_backward,
+ *                          their ..64_f32 forms and oracle_klstm_cell64_backward
+ *                          are the same code on 64-interval tables (pinned
+ *                          through a 64-interval table that repeats Table 1,
+ *                          which must give the 32-interval gradients, and by
+ *                          hand-worked values)
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
@@ -559,12 +565,13 @@ void oracle_ksigmoid_backward(const uint16_t *dy, const uint16_t *sg, uint16_t *
 
 /* dx = dy * Swish'(x), Swish'(x) = s + x*(s*(1 - s)), with s = Sigmoid(x)
  * recomputed from x through K-TanH exactly as oracle_kswish forms it. */
-void oracle_kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
-                            const oracle_lut *lut)
+static void kswish_backward_fields(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                                   unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                   const int8_t *Tb)
 {
     for (size_t i = 0; i < n; ++i) {
         float xv = widen(x[i]);
-        float sg = ksigmoid_f32_of_bf16(x[i], lut);
+        float sg = ksigmoid_fields(x[i], s, TE, Tr, Tb);
         float one_minus = 1.0f - sg;
         float bell = sg * one_minus;
         float xbell = xv * bell;
@@ -574,12 +581,19 @@ void oracle_kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
     }
 }
 
+void oracle_kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                            const oracle_lut *lut)
+{
+    kswish_backward_fields(dy, x, dx, n, 3, lut->E, lut->r, lut->b);
+}
+
 /* dx = dy * GELU'(x) for the tanh form: with u = c*(x + a*x^3) and t = TanH(u)
  * (K-TanH on the BFloat16 value of u, as oracle_kgelu forms it),
  *   GELU'(x) = 0.5*(1 + t) + (0.5*x) * ((1 - t*t) * (c*(1 + 3a*x^2))),
  * 3a written as the Float32 constant 0.134145. */
-void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
-                           const oracle_lut *lut)
+static void kgelu_backward_fields(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                                  unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                  const int8_t *Tb)
 {
     const float a = 0.044715f;
     const float a3 = 0.134145f;
@@ -591,7 +605,7 @@ void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, 
         float ax3 = a * x3;
         float inner = xv + ax3;
         float arg = c * inner;
-        float th = widen(ktanh_bf16_scalar(narrow_rne(arg), lut));
+        float th = widen(ktanh_bf16_fields(narrow_rne(arg), s, TE, Tr, Tb));
         float one_plus = 1.0f + th;
         float left = 0.5f * one_plus;
         float th2 = th * th;
@@ -606,6 +620,25 @@ void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, 
         float g = widen(dy[i]) * slope;
         dx[i] = narrow_rne(g);
     }
+}
+
+void oracle_kgelu_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                           const oracle_lut *lut)
+{
+    kgelu_backward_fields(dy, x, dx, n, 3, lut->E, lut->r, lut->b);
+}
+
+/* The same two on 64-interval tables: same code, 4 index bits. */
+void oracle_kswish64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                              const oracle_lut64 *lut)
+{
+    kswish_backward_fields(dy, x, dx, n, 4, lut->E, lut->r, lut->b);
+}
+
+void oracle_kgelu64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                             const oracle_lut64 *lut)
+{
+    kgelu_backward_fields(dy, x, dx, n, 4, lut->E, lut->r, lut->b);
 }
 
 /* The same four gradients on Float32 tensors: nothing is rounded to BFloat16, the
@@ -628,11 +661,12 @@ void oracle_ksigmoid_f32_backward(const float *dy, const float *sg, float *dx, s
     }
 }
 
-void oracle_kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
-                                const oracle_lut *lut)
+static void kswish_f32_backward_fields(const float *dy, const float *x, float *dx, size_t n,
+                                       unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                       const int8_t *Tb)
 {
     for (size_t i = 0; i < n; ++i) {
-        float sg = ksigmoid_f32_fields(x[i], 3, lut->E, lut->r, lut->b);
+        float sg = ksigmoid_f32_fields(x[i], s, TE, Tr, Tb);
         float one_minus = 1.0f - sg;
         float bell = sg * one_minus;
         float xbell = x[i] * bell;
@@ -641,8 +675,15 @@ void oracle_kswish_f32_backward(const float *dy, const float *x, float *dx, size
     }
 }
 
-void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_t n,
-                               const oracle_lut *lut)
+void oracle_kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                const oracle_lut *lut)
+{
+    kswish_f32_backward_fields(dy, x, dx, n, 3, lut->E, lut->r, lut->b);
+}
+
+static void kgelu_f32_backward_fields(const float *dy, const float *x, float *dx, size_t n,
+                                      unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                      const int8_t *Tb)
 {
     const float a = 0.044715f;
     const float a3 = 0.134145f;
@@ -654,7 +695,7 @@ void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_
         float ax3 = a * x3;
         float inner = xv + ax3;
         float arg = c * inner;
-        float th = f32_of_bits(ktanh_f32_scalar(bits_of_f32(arg), lut));
+        float th = f32_of_bits(ktanh_f32_fields(bits_of_f32(arg), s, TE, Tr, Tb));
         float one_plus = 1.0f + th;
         float left = 0.5f * one_plus;
         float th2 = th * th;
@@ -670,6 +711,25 @@ void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_
     }
 }
 
+void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                               const oracle_lut *lut)
+{
+    kgelu_f32_backward_fields(dy, x, dx, n, 3, lut->E, lut->r, lut->b);
+}
+
+/* The same two on 64-interval tables. */
+void oracle_kswish64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                  const oracle_lut64 *lut)
+{
+    kswish_f32_backward_fields(dy, x, dx, n, 4, lut->E, lut->r, lut->b);
+}
+
+void oracle_kgelu64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                 const oracle_lut64 *lut)
+{
+    kgelu_f32_backward_fields(dy, x, dx, n, 4, lut->E, lut->r, lut->b);
+}
+
 /* One LSTM-cell step backwards.  The forward activations are recomputed from
  * the gate pre-activations with K-TanH, exactly as oracle_klstm_cell forms them.
  *   gates   [B][4H] BFloat16 (i|f|g|o)      c_prev  [B][H] Float32
@@ -679,23 +739,24 @@ void oracle_kgelu_f32_backward(const float *dy, const float *x, float *dx, size_
  *   do = dh*tc                dc = dc_next + (dh*o)*(1 - tc*tc)
  *   di = dc*g   df = dc*c_prev   dg = dc*i   dc_prev = dc*f
  *   d(gate pre-activations) = di*(i*(1-i)) | df*(f*(1-f)) | dg*(1 - g*g) | do*(o*(1-o)) */
-void oracle_klstm_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
-                                const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
-                                size_t H, const oracle_lut *lut)
+static void klstm_backward_fields(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                  const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                  size_t H, unsigned s, const uint8_t *TE, const uint8_t *Tr,
+                                  const int8_t *Tb)
 {
     for (size_t bi = 0; bi < B; ++bi) {
         const uint16_t *row = gates + bi * 4 * H;
         uint16_t *drow = dgates + bi * 4 * H;
         for (size_t j = 0; j < H; ++j) {
-            float ig = ksigmoid_f32_of_bf16(row[0 * H + j], lut);
-            float fg = ksigmoid_f32_of_bf16(row[1 * H + j], lut);
-            float gg = widen(ktanh_bf16_scalar(row[2 * H + j], lut));
-            float og = ksigmoid_f32_of_bf16(row[3 * H + j], lut);
+            float ig = ksigmoid_fields(row[0 * H + j], s, TE, Tr, Tb);
+            float fg = ksigmoid_fields(row[1 * H + j], s, TE, Tr, Tb);
+            float gg = widen(ktanh_bf16_fields(row[2 * H + j], s, TE, Tr, Tb));
+            float og = ksigmoid_fields(row[3 * H + j], s, TE, Tr, Tb);
             float c0 = c_prev[bi * H + j];
             float keep = fg * c0;
             float add = ig * gg;
             float c1 = keep + add;
-            float tc = widen(ktanh_bf16_scalar(narrow_rne(c1), lut));
+            float tc = widen(ktanh_bf16_fields(narrow_rne(c1), s, TE, Tr, Tb));
             float dhv = widen(dh[bi * H + j]);
 
             float d_o = dhv * tc;
@@ -720,6 +781,23 @@ void oracle_klstm_cell_backward(const uint16_t *gates, const float *c_prev, cons
             drow[3 * H + j] = narrow_rne(d_o * oslope);
         }
     }
+}
+
+void oracle_klstm_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                size_t H, const oracle_lut *lut)
+{
+    klstm_backward_fields(gates, c_prev, dh, dc_next, dgates, dc_prev, B, H, 3, lut->E, lut->r,
+                          lut->b);
+}
+
+/* The same step with 64-interval tables. */
+void oracle_klstm_cell64_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                  const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                  size_t H, const oracle_lut64 *lut)
+{
+    klstm_backward_fields(gates, c_prev, dh, dc_next, dgates, dc_prev, B, H, 4, lut->E, lut->r,
+                          lut->b);
 }
 
 /* ------------------------------------------------------------------ */

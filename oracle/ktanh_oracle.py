@@ -114,6 +114,13 @@ def _load():
             getattr(lib, name).restype = None
         lib.oracle_klstm_cell_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz, lp]
         lib.oracle_klstm_cell_backward.restype = None
+        for name in ("oracle_kswish64_backward", "oracle_kgelu64_backward",
+                     "oracle_kswish64_f32_backward", "oracle_kgelu64_f32_backward"):
+            getattr(lib, name).argtypes = [vp, vp, vp, sz, ctypes.POINTER(OracleLut64)]
+            getattr(lib, name).restype = None
+        lib.oracle_klstm_cell64_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz,
+                                                     ctypes.POINTER(OracleLut64)]
+        lib.oracle_klstm_cell64_backward.restype = None
         lp64 = ctypes.POINTER(OracleLut64)
         lib.oracle_fit_lut64.argtypes = [lp64]
         for name in ("oracle_ktanh64_bf16", "oracle_ktanh64_f32", "oracle_ksigmoid64", "oracle_kswish64",
@@ -326,12 +333,13 @@ def ksigmoid_backward(dy_bits, s_bits):
     return _backward("oracle_ksigmoid_backward", dy_bits, s_bits)
 
 
-def _backward_from_input(name, dy_bits, x_bits, lut):
+def _backward_from_input(name, dy_bits, x_bits, lut, wide=False):
     dy = np.ascontiguousarray(dy_bits, dtype=np.uint16)
     x = np.ascontiguousarray(x_bits, dtype=np.uint16)
     assert dy.shape == x.shape
     dx = np.empty_like(dy)
-    lut = table1() if lut is None else lut
+    if lut is None:
+        lut = fit_lut64() if wide else table1()
     getattr(_load(), name)(dy.ctypes.data, x.ctypes.data, dx.ctypes.data, dy.size, ctypes.byref(lut))
     return dx
 
@@ -346,13 +354,24 @@ def kgelu_backward(dy_bits, x_bits, lut=None):
     return _backward_from_input("oracle_kgelu_backward", dy_bits, x_bits, lut)
 
 
-def _f32_backward(name, dy, v, lut=None, with_lut=False):
+def kswish64_backward(dy_bits, x_bits, lut64=None):
+    """kswish_backward with a 64-interval table (None = the fitted one)."""
+    return _backward_from_input("oracle_kswish64_backward", dy_bits, x_bits, lut64, wide=True)
+
+
+def kgelu64_backward(dy_bits, x_bits, lut64=None):
+    """kgelu_backward with a 64-interval table (None = the fitted one)."""
+    return _backward_from_input("oracle_kgelu64_backward", dy_bits, x_bits, lut64, wide=True)
+
+
+def _f32_backward(name, dy, v, lut=None, with_lut=False, wide=False):
     dy = np.ascontiguousarray(dy, dtype=np.float32)
     v = np.ascontiguousarray(v, dtype=np.float32)
     assert dy.shape == v.shape
     dx = np.empty_like(dy)
     if with_lut:
-        lut = table1() if lut is None else lut
+        if lut is None:
+            lut = fit_lut64() if wide else table1()
         getattr(_load(), name)(dy.ctypes.data, v.ctypes.data, dx.ctypes.data, dy.size, ctypes.byref(lut))
     else:
         getattr(_load(), name)(dy.ctypes.data, v.ctypes.data, dx.ctypes.data, dy.size)
@@ -379,7 +398,25 @@ def kgelu_f32_backward(dy, x, lut=None):
     return _f32_backward("oracle_kgelu_f32_backward", dy, x, lut, True)
 
 
-def klstm_cell_backward(gates_bits, c_prev, dh_bits, dc_next, lut=None):
+def kswish64_f32_backward(dy, x, lut64=None):
+    """kswish_f32_backward with a 64-interval table (None = the fitted one)."""
+    return _f32_backward("oracle_kswish64_f32_backward", dy, x, lut64, True, wide=True)
+
+
+def kgelu64_f32_backward(dy, x, lut64=None):
+    """kgelu_f32_backward with a 64-interval table (None = the fitted one)."""
+    return _f32_backward("oracle_kgelu64_f32_backward", dy, x, lut64, True, wide=True)
+
+
+def klstm_cell64_backward(gates_bits, c_prev, dh_bits, dc_next, lut64=None):
+    """klstm_cell_backward with a 64-interval table (None = the fitted one)."""
+    return klstm_cell_backward(gates_bits, c_prev, dh_bits, dc_next,
+                               fit_lut64() if lut64 is None else lut64,
+                               _entry="oracle_klstm_cell64_backward")
+
+
+def klstm_cell_backward(gates_bits, c_prev, dh_bits, dc_next, lut=None,
+                        _entry="oracle_klstm_cell_backward"):
     """One LSTM-cell step backwards.  gates uint16 [B, 4H], c_prev/dc_next float32 [B, H],
     dh uint16 [B, H].  Returns (dgates uint16 [B, 4H], dc_prev float32 [B, H])."""
     gates = np.ascontiguousarray(gates_bits, dtype=np.uint16)
@@ -392,7 +429,7 @@ def klstm_cell_backward(gates_bits, c_prev, dh_bits, dc_next, lut=None):
     dgates = np.empty_like(gates)
     dc_prev = np.empty_like(c_prev)
     lut = table1() if lut is None else lut
-    _load().oracle_klstm_cell_backward(gates.ctypes.data, c_prev.ctypes.data, dh.ctypes.data,
-                                       dc_next.ctypes.data, dgates.ctypes.data, dc_prev.ctypes.data,
-                                       B, H, ctypes.byref(lut))
+    getattr(_load(), _entry)(gates.ctypes.data, c_prev.ctypes.data, dh.ctypes.data,
+                             dc_next.ctypes.data, dgates.ctypes.data, dc_prev.ctypes.data,
+                             B, H, ctypes.byref(lut))
     return dgates, dc_prev

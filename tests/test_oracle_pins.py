@@ -756,6 +756,87 @@ def test_f32_backward_functions(oracle):
     assert np.max(np.abs(oracle.ksigmoid_f32_backward(ones, s) - s_true * (1 - s_true))) <= 1.67e-2 / 2 + 1e-6
 
 
+def test_gradients_on_64_interval_tables(oracle):
+    """The Swish, GELU and LSTM-cell gradients with 64-interval tables inside.  A 64-interval table
+    that repeats every entry of Table 1 twice describes the same function, so it must give the
+    32-interval gradients (pinned above) bit for bit; with the fitted table, values by hand that the
+    32-interval table does not produce, and float64 re-evaluation around the pinned 64-interval K-TanH."""
+    doubled = oracle.OracleLut64.from_tuples([oracle.table1().as_tuples()[((t >> 4) << 3) | ((t & 15) >> 1)] for t in range(64)])
+    x = wl.all_bf16_patterns()
+    rng = np.random.Generator(np.random.PCG64(40))
+    dy = wl.f32_to_bf16_bits(rng.standard_normal(x.size, dtype=np.float32))
+    for name in ("kswish", "kgelu"):
+        a = getattr(oracle, name + "64_backward")(dy, x, doubled)
+        b = getattr(oracle, name + "_backward")(dy, x)
+        an, bn = (a & 0x7FFF) > 0x7F80, (b & 0x7FFF) > 0x7F80
+        assert np.array_equal(an, bn) and np.array_equal(a[~an], b[~bn]), name
+    u = np.concatenate([np.arange(1 << 16, dtype=np.uint32) << 16,
+                        rng.integers(0, 1 << 32, size=1 << 17, dtype=np.uint64).astype(np.uint32),
+                        wl.f32_mixture(1 << 17, seed=41)])
+    u = u[(u & 0x7FFFFFFF) < 0x7F800000]
+    xf = u.view(np.float32)
+    dyf = rng.standard_normal(xf.size, dtype=np.float32)
+    with np.errstate(all="ignore"):
+        for name in ("kswish", "kgelu"):
+            a = getattr(oracle, name + "64_f32_backward")(dyf, xf, doubled)
+            b = getattr(oracle, name + "_f32_backward")(dyf, xf)
+            assert np.all((a.view(np.uint32) == b.view(np.uint32)) | (np.isnan(a) & np.isnan(b))), name
+    g3, c0 = wl.lstm_cell_inputs(1, 5, 24)
+    dh = wl.f32_to_bf16_bits(rng.standard_normal((5, 24), dtype=np.float32))
+    dcn = rng.standard_normal((5, 24), dtype=np.float32)
+    dg_a, dc_a = oracle.klstm_cell64_backward(g3[0], c0, dh, dcn, doubled)
+    dg_b, dc_b = oracle.klstm_cell_backward(g3[0], c0, dh, dcn)
+    assert np.array_equal(dg_a, dg_b) and np.array_equal(dc_a, dc_b)
+
+    # By hand with the fitted table.  Its entries used below:
+    fit = oracle.fit_lut64().as_tuples()
+    assert fit[24] == (125, 0, -9) and fit[32] == (125, 0, 111) and fit[35] == (126, 1, -3)
+    one, x075 = np.array([0x3F80], np.uint16), np.array([0x3F40], np.uint16)
+    # Swish' at x = 0.75: x/2 = 0.375 = (125, M 64) -> t = 1 0000 + 1000 = 24 -> M_o = 64 - 9 = 55:
+    #   K = 2^-2 * (1 + 55/128) = 183/512;  s = 695/1024;  s(1-s) = 695*329/2^20 = 228655/2^20;
+    #   slope = 695/1024 + 0.75 * 228655/2^20 = 3532685/2^22 = 0.842257738 (exact in Float32)
+    #   = 1.684515 * 2^-1 -> mantissa 87.62 -> 88 -> 0x3F58   (Table 1 gives 0x3F57)
+    assert oracle.kswish64_backward(one, x075)[0] == 0x3F58 and oracle.kswish_backward(one, x075)[0] == 0x3F57
+    assert oracle.kswish64_backward(np.array([0x4000], np.uint16), x075)[0] == 0x3FD8
+    assert oracle.kswish64_f32_backward(np.ones(2, np.float32), np.array([0.75, 1.0], np.float32)).tolist() == \
+        [3532685 / 4194304, 974047 / 1048576]      # at x = 1: s = 751/1024 (K64(0.5) = 239/512), slope = 751/1024 + 751*273/2^20
+    # GELU' at x = 0.75: argument c*(x + a x^3) = 0.61346483 -> BFloat16 0x3F1D = (126, M 29) -> t = 10 0000 + 0011 = 35
+    #   -> M_o = (29 >> 1) - 3 = 11: K = 2^-1 * (1 + 11/128) = 139/256 = 0.54296875
+    #   slope = 0.5*(1 + K) + 0.375 * (1 - K^2) * c*(1 + 0.134145 * 0.5625)
+    #         = 0.771484375 + 0.375 * 0.705184937 * 0.858090187 = 0.998401 -> mantissa 127.59 -> rounds up to 1.0
+    assert oracle.kgelu64_backward(one, x075)[0] == 0x3F80 and oracle.kgelu_backward(one, x075)[0] == 0x3F7F
+    #   Float32 tensor: the argument keeps its low bits, M23 = 0x1D0C08: M_o = (M23 >> 1) - 3 * 2^16 = 0x0B8604,
+    #   K = 0.5 * (1 + 755204/2^23) = 0.545013666;  slope = 0.772506833 + 0.375 * 0.702960104 * 0.858090187 = 0.998708
+    assert abs(float(oracle.kgelu64_f32_backward(np.ones(1, np.float32), np.array([0.75], np.float32))[0]) - 0.998708) < 2e-6
+    # LSTM cell: gates 0, c = 1, dh = 1, dc_next = 0 -> i = f = o = 0.5, g = 0, c' = 0.5, tc = K64(0.5) = 239/512;
+    #   do = 239/512, dc = 0.5 * (1 - 57121/262144) = 205023/524288;  dgates = (0, dc/4, dc/2, do/4):
+    #   dc/4 = 1.5642 * 2^-4 -> 0x3DC8, dc/2 -> 0x3E48, do/4 = 1.8671875 * 2^-4 -> mantissa 111 exactly -> 0x3DEF
+    #   (Table 1: 0x3DF0);  dc_prev = dc * 0.5 = 205023/1048576
+    H = 8
+    dg, dcp = oracle.klstm_cell64_backward(np.zeros((1, 4 * H), np.uint16), np.ones((1, H), np.float32),
+                                           np.full((1, H), 0x3F80, np.uint16), np.zeros((1, H), np.float32))
+    assert np.all(dg[0, :H] == 0) and np.all(dg[0, H:2 * H] == 0x3DC8) and np.all(dg[0, 2 * H:3 * H] == 0x3E48)
+    assert np.all(dg[0, 3 * H:] == 0x3DEF) and np.all(dcp == np.float32(205023 / 1048576))
+
+    # float64 re-evaluation around the pinned 64-interval K-TanH
+    xb = _finite_bf16()
+    xv, dv = _bf16_val(xb), _bf16_val(dy[:xb.size])
+    k = _bf16_val(oracle.ktanh64_bf16(_round_f64_to_bf16(xv / 2)))
+    sg = (1.0 + k) / 2.0
+    with np.errstate(over="ignore", invalid="ignore"):
+        want = dv * (sg + xv * (sg * (1.0 - sg)))
+    ok = np.isfinite(want) & (np.abs(want) < 3.0e38)
+    assert np.max(_ulp_distance_bf16(oracle.kswish64_backward(dy[:xb.size], xb)[ok], _round_f64_to_bf16(want[ok]))) <= 1
+    xf = xv.astype(np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        arg32 = np.float32(0.7978845608028654) * (xf + np.float32(0.044715) * ((xf * xf) * xf))
+        t = _bf16_val(oracle.ktanh64_bf16(wl.f32_to_bf16_bits(arg32)))
+        want = dv * (0.5 * (1.0 + t) + 0.5 * xv * ((1.0 - t * t) * (np.sqrt(2.0 / np.pi) * (1.0 + 0.134145 * xv * xv))))
+    ok = np.isfinite(want) & (np.abs(want) < 3.0e38) & (np.abs(xv) < 1e18)
+    got = oracle.kgelu64_backward(dy[:xb.size], xb)
+    assert np.all(np.abs(_bf16_val(got[ok]) - want[ok]) <= 2.0 ** -8 * np.abs(want[ok]) + 1e-6 * np.abs(dv[ok]) * (1 + np.abs(xv[ok]) ** 3))
+
+
 def test_checksums_against_an_independent_implementation(oracle):
     """All 65,536 outputs of the four BFloat16 operations, as CRC32, against values recorded from
     an implementation that shares nothing with this oracle."""
