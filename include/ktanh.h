@@ -53,7 +53,9 @@ typedef enum ktanh_status {
     KT_ERR_NULL = 1,  /* a required pointer is NULL                                       */
     KT_ERR_ALIGN = 2, /* a tensor pointer is not aligned to its element size              */
     KT_ERR_LUT = 3,   /* the table fails ktanh_lut_validate                               */
-    KT_ERR_SHAPE = 4, /* klstm_cell: H not a multiple of 8; any entry point: tensor too large */
+    KT_ERR_SHAPE = 4, /* klstm_cell: H not a multiple of 8; any entry point: tensor too large
+                         (one call covers fewer than 2^26 wavefront tiles of 1 KiB of output,
+                         i.e. just under 64 GiB; the LSTM cell fewer than 2^29 cells per step) */
     KT_ERR_HIP = 5    /* the HIP runtime refused the launch                               */
 } ktanh_status_t;
 
@@ -102,13 +104,6 @@ ktanh_status_t kswish(const uint16_t *in, uint16_t *out, size_t n, const ktanh_l
 ktanh_status_t kgelu(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut_t *lut,
                      ktanh_stream_t stream);
 
-/* Not an operation of the paper: copies n 16-bit elements with exactly the accesses of ktanh_bf16
- * (same launch shape, same load and store policies) and no arithmetic.  It is the yardstick the
- * benchmark reports next to the K-TanH figures -- what the memory system allows for this launch --
- * and a device-to-device copy that is faster than the runtime's own on large buffers.
- * in, out: device, n elements each, 2-byte aligned; out == in allowed. */
-ktanh_status_t ktanh_stream_copy(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
-
 /* ---- 64-interval variant ------------------------------------------------------------------------
  * Section 2.4 (last paragraph): the parameters are 8-bit, so 64 intervals fit where AVX512 held 32
  * 16-bit values.  Index t = (2 LSBs of E_i) << 4 | (4 MSBs of M_i); t = 16..31 covers [0.25, 0.5),
@@ -143,8 +138,7 @@ ktanh_status_t ktanh64_f32(const uint32_t *in, uint32_t *out, size_t n, const kt
                            ktanh_stream_t stream);
 
 /* ksigmoid, kswish, kgelu and klstm_cell (declared below and above) with a 64-interval table: same
- * contracts, same operation sequences, K = ktanh64_bf16.  (The Float32-tensor activations exist for
- * 32-interval tables only.) */
+ * contracts, same operation sequences, K = ktanh64_bf16. */
 ktanh_status_t ksigmoid64(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
                           ktanh_stream_t stream);
 ktanh_status_t kswish64(const uint16_t *in, uint16_t *out, size_t n, const ktanh_lut64_t *lut,
@@ -196,8 +190,8 @@ ktanh_status_t ktanh_f32_to_bf16(const float *in, uint16_t *out, size_t n, const
  * Per cell and step, in Float32:  i, f, o = 0.5*K(0.5 g_.)+0.5;  g = K(g_g);
  *   c' = (f*c) + (i*g);  h' = bf16(o * K(bf16(c'))).   The state is carried in registers between
  * the T steps.  T == 1 is the ordinary per-step call of a recurrent network.
- * H must be a multiple of 8 (KT_ERR_SHAPE); all four tensors need 16-byte alignment
- * (KT_ERR_ALIGN). */
+ * H must be a multiple of 8 (KT_ERR_SHAPE).  The kernel moves BFloat16 pairs and Float32 pairs:
+ * gates and h_out must be 4-byte aligned, c_in and c_out 8-byte aligned (KT_ERR_ALIGN). */
 ktanh_status_t klstm_cell(const uint16_t *gates, const float *c_in, float *c_out, uint16_t *h_out,
                           size_t T, size_t B, size_t H, const ktanh_lut_t *lut,
                           ktanh_stream_t stream);
@@ -250,10 +244,28 @@ ktanh_status_t kgelu_f32_backward(const float *dy, const float *x, float *dx, si
  *   gates   [B][4H] BFloat16 (i|f|g|o), device     c_prev  [B][H] Float32, device
  *   dh      [B][H]  BFloat16, device               dc_next [B][H] Float32, device
  *   dgates  [B][4H] BFloat16, device, out          dc_prev [B][H] Float32, device, out (may be dc_next)
- * H must be a multiple of 8 (KT_ERR_SHAPE); all tensors 16-byte aligned (KT_ERR_ALIGN). */
+ * H must be a multiple of 8 (KT_ERR_SHAPE); gates, dh and dgates 4-byte aligned, c_prev, dc_next and
+ * dc_prev 8-byte aligned (KT_ERR_ALIGN). */
 ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
                                    const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
                                    size_t H, const ktanh_lut_t *lut, ktanh_stream_t stream);
+
+
+/* The gradients that read a table, with a 64-interval table (Section 2.4, last paragraph) inside:
+ * the same formulas and operation order with K = ktanh64_bf16 (ktanh64_f32 on Float32 tensors).
+ * `lut` == NULL selects the fitted 64-interval table.  (ktanh_bf16_backward, ksigmoid_backward and
+ * their Float32 forms take the forward output and read no table: they serve both table sizes.) */
+ktanh_status_t kswish64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                                 const ktanh_lut64_t *lut, ktanh_stream_t stream);
+ktanh_status_t kgelu64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx, size_t n,
+                                const ktanh_lut64_t *lut, ktanh_stream_t stream);
+ktanh_status_t kswish64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                     const ktanh_lut64_t *lut, ktanh_stream_t stream);
+ktanh_status_t kgelu64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                    const ktanh_lut64_t *lut, ktanh_stream_t stream);
+ktanh_status_t klstm_cell64_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                     const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                     size_t H, const ktanh_lut64_t *lut, ktanh_stream_t stream);
 
 #ifdef __cplusplus
 }

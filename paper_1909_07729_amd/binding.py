@@ -16,16 +16,27 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libktanh.so")
 INTERVALS = 32
 
-EXPORTS = ("ktanh_status_string", "ktanh_default_lut", "ktanh_lut_validate", "ktanh_bf16",
-           "ktanh_f32", "ksigmoid", "kswish", "kgelu", "klstm_cell",
-           "ktanh_fit_lut", "ktanh_fit_lut64", "ktanh_lut64_validate", "ktanh64_bf16", "ktanh64_f32",
-           "ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16",
-           "ksigmoid64", "kswish64", "kgelu64", "klstm_cell64",
-           "ktanh_bf16_backward", "ksigmoid_backward", "klstm_cell_backward",
-           "kswish_backward", "kgelu_backward", "ktanh_fit_lut_bmin0",
-           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
-           "ktanh_stream_copy")
+# Every function include/ktanh.h declares, with the kinds of its parameters:
+#   p = device tensor pointer, n = size_t, l = table pointer (32 intervals), L = table pointer (64),
+#   s = stream, i = int status.  The ctypes prototypes below are built from these strings and nothing else.
+SIGNATURES = {
+    "ktanh_status_string": "i", "ktanh_default_lut": "", "ktanh_lut_validate": "l",
+    "ktanh_lut64_validate": "L", "ktanh_fit_lut": "l", "ktanh_fit_lut64": "L", "ktanh_fit_lut_bmin0": "l",
+    "ktanh_bf16": "ppnls", "ktanh_f32": "ppnls", "ksigmoid": "ppnls", "kswish": "ppnls", "kgelu": "ppnls",
+    "ktanh64_bf16": "ppnLs", "ktanh64_f32": "ppnLs", "ksigmoid64": "ppnLs", "kswish64": "ppnLs",
+    "kgelu64": "ppnLs",
+    "ksigmoid_f32": "ppnls", "kswish_f32": "ppnls", "kgelu_f32": "ppnls", "ktanh_f32_to_bf16": "ppnls",
+    "ksigmoid64_f32": "ppnLs", "kswish64_f32": "ppnLs", "kgelu64_f32": "ppnLs",
+    "klstm_cell": "ppppnnnls", "klstm_cell64": "ppppnnnLs",
+    "ktanh_bf16_backward": "pppns", "ksigmoid_backward": "pppns",
+    "ktanh_f32_backward": "pppns", "ksigmoid_f32_backward": "pppns",
+    "kswish_backward": "pppnls", "kgelu_backward": "pppnls",
+    "kswish_f32_backward": "pppnls", "kgelu_f32_backward": "pppnls",
+    "kswish64_backward": "pppnLs", "kgelu64_backward": "pppnLs",
+    "kswish64_f32_backward": "pppnLs", "kgelu64_f32_backward": "pppnLs",
+    "klstm_cell_backward": "ppppppnnls", "klstm_cell64_backward": "ppppppnnLs",
+}
+EXPORTS = tuple(SIGNATURES)
 
 
 class KtanhLut(ctypes.Structure):
@@ -85,57 +96,14 @@ def load_library() -> ctypes.CDLL:
             raise FileNotFoundError(
                 f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
         lib = ctypes.CDLL(LIB_PATH)
-        lp, vp, sz = ctypes.POINTER(KtanhLut), ctypes.c_void_p, ctypes.c_size_t
-        lib.ktanh_status_string.argtypes = [ctypes.c_int]
+        kinds = {"p": ctypes.c_void_p, "n": ctypes.c_size_t, "s": ctypes.c_void_p, "i": ctypes.c_int,
+                 "l": ctypes.POINTER(KtanhLut), "L": ctypes.POINTER(KtanhLut64)}
+        for name, params in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.argtypes = [kinds[k] for k in params]
+            fn.restype = ctypes.c_int
         lib.ktanh_status_string.restype = ctypes.c_char_p
-        lib.ktanh_default_lut.argtypes = []
-        lib.ktanh_default_lut.restype = lp
-        lib.ktanh_lut_validate.argtypes = [lp]
-        lib.ktanh_lut_validate.restype = ctypes.c_int
-        for name in ("ktanh_bf16", "ktanh_f32", "ksigmoid", "kswish", "kgelu"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, sz, lp, vp]
-            fn.restype = ctypes.c_int
-        lib.klstm_cell.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp, vp]
-        lib.klstm_cell.restype = ctypes.c_int
-        for name in ("ksigmoid_f32", "kswish_f32", "kgelu_f32", "ktanh_f32_to_bf16"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, sz, lp, vp]
-            fn.restype = ctypes.c_int
-        lp64 = ctypes.POINTER(KtanhLut64)
-        lib.ktanh_fit_lut.argtypes = [lp]
-        lib.ktanh_fit_lut.restype = ctypes.c_int
-        lib.ktanh_fit_lut_bmin0.argtypes = [lp]
-        lib.ktanh_fit_lut_bmin0.restype = ctypes.c_int
-        lib.ktanh_fit_lut64.argtypes = [lp64]
-        lib.ktanh_fit_lut64.restype = ctypes.c_int
-        lib.ktanh_lut64_validate.argtypes = [lp64]
-        lib.ktanh_lut64_validate.restype = ctypes.c_int
-        for name in ("ktanh64_bf16", "ktanh64_f32", "ksigmoid64", "kswish64", "kgelu64",
-                     "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
-           "ktanh_stream_copy"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, sz, lp64, vp]
-            fn.restype = ctypes.c_int
-        lib.ktanh_stream_copy.argtypes = [vp, vp, sz, vp]
-        lib.ktanh_stream_copy.restype = ctypes.c_int
-        lib.klstm_cell64.argtypes = [vp, vp, vp, vp, sz, sz, sz, lp64, vp]
-        lib.klstm_cell64.restype = ctypes.c_int
-        for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, vp, sz, vp]
-            fn.restype = ctypes.c_int
-        for name in ("kswish_backward", "kgelu_backward", "kswish_f32_backward", "kgelu_f32_backward"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, vp, sz, lp, vp]
-            fn.restype = ctypes.c_int
-        for name in ("ktanh_f32_backward", "ksigmoid_f32_backward"):
-            fn = getattr(lib, name)
-            fn.argtypes = [vp, vp, vp, sz, vp]
-            fn.restype = ctypes.c_int
-        lib.klstm_cell_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz, lp, vp]
-        lib.klstm_cell_backward.restype = ctypes.c_int
+        lib.ktanh_default_lut.restype = ctypes.POINTER(KtanhLut)
         _lib = lib
     return _lib
 
@@ -170,10 +138,7 @@ def ktanh_fit_lut_bmin0() -> KtanhLut:
     lut = KtanhLut()
     st = load_library().ktanh_fit_lut_bmin0(ctypes.byref(lut))
     if st != 0:
-        raise KtanhError(st, "ktanh_fit_lut_bmin0",
-           "ksigmoid64_f32", "kswish64_f32", "kgelu64_f32",
-           "ktanh_f32_backward", "ksigmoid_f32_backward", "kswish_f32_backward", "kgelu_f32_backward",
-           "ktanh_stream_copy")
+        raise KtanhError(st, "ktanh_fit_lut_bmin0")
     return lut
 
 
@@ -229,20 +194,6 @@ def _elementwise(name, x, out, lut, stream, dtypes):
 def ktanh_bf16(x, out=None, lut=None, stream=None):
     """K-TanH on a BFloat16 tensor (or its int16/uint16 bit view); ``out`` may be ``x``."""
     return _elementwise("ktanh_bf16", x, out, lut, stream, _BF16_VIEWS)
-
-
-def ktanh_stream_copy(x, out=None, stream=None):
-    """Copies a 16-bit tensor with the accesses of ``ktanh_bf16`` and no arithmetic (the yardstick)."""
-    _check(x, _BF16_VIEWS, "in")
-    if out is None:
-        out = torch.empty_like(x)
-    _check(out, _BF16_VIEWS, "out")
-    if out.numel() != x.numel():
-        raise ValueError("in and out differ in size")
-    st = load_library().ktanh_stream_copy(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
-    if st != 0:
-        raise KtanhError(st, "ktanh_stream_copy")
-    return out
 
 
 def ktanh_f32(x, out=None, lut=None, stream=None):
@@ -409,6 +360,16 @@ def kgelu_backward(dy, x, dx=None, lut=None, stream=None):
     return _backward_from_input("kgelu_backward", dy, x, dx, lut, stream)
 
 
+def kswish64_backward(dy, x, dx=None, lut=None, stream=None):
+    """``kswish_backward`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return _backward_from_input("kswish64_backward", dy, x, dx, lut, stream)
+
+
+def kgelu64_backward(dy, x, dx=None, lut=None, stream=None):
+    """``kgelu_backward`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return _backward_from_input("kgelu64_backward", dy, x, dx, lut, stream)
+
+
 def _backward_f32(name, dy, v, dx, lut, stream, with_lut):
     for t, what in ((dy, "dy"), (v, "the second input")):
         _check(t, (torch.float32,), what)
@@ -446,7 +407,24 @@ def kgelu_f32_backward(dy, x, dx=None, lut=None, stream=None):
     return _backward_f32("kgelu_f32_backward", dy, x, dx, lut, stream, True)
 
 
-def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None):
+def kswish64_f32_backward(dy, x, dx=None, lut=None, stream=None):
+    """``kswish_f32_backward`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return _backward_f32("kswish64_f32_backward", dy, x, dx, lut, stream, True)
+
+
+def kgelu64_f32_backward(dy, x, dx=None, lut=None, stream=None):
+    """``kgelu_f32_backward`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return _backward_f32("kgelu64_f32_backward", dy, x, dx, lut, stream, True)
+
+
+def klstm_cell64_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None):
+    """``klstm_cell_backward`` with a 64-interval table (``KtanhLut64``; None = the fitted one)."""
+    return klstm_cell_backward(gates, c_prev, dh, dc_next, dgates, dc_prev, lut, stream,
+                               _entry="klstm_cell64_backward")
+
+
+def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, lut=None, stream=None,
+                        _entry="klstm_cell_backward"):
     """One LSTM-cell step backwards.  gates [B, 4H] BFloat16, c_prev and dc_next [B, H] Float32,
     dh [B, H] BFloat16.  Returns (dgates [B, 4H], dc_prev [B, H])."""
     _check(gates, _BF16_VIEWS, "gates")
@@ -467,9 +445,9 @@ def klstm_cell_backward(gates, c_prev, dh, dc_next, dgates=None, dc_prev=None, l
     _check(dc_prev, (torch.float32,), "dc_prev")
     if tuple(dgates.shape) != (B, H4) or tuple(dc_prev.shape) != (B, H):
         raise ValueError("dgates must be [B, 4H] and dc_prev [B, H]")
-    st = load_library().klstm_cell_backward(gates.data_ptr(), c_prev.data_ptr(), dh.data_ptr(),
-                                            dc_next.data_ptr(), dgates.data_ptr(), dc_prev.data_ptr(),
-                                            B, H, _lut_arg(lut), _stream_handle(stream))
+    st = getattr(load_library(), _entry)(gates.data_ptr(), c_prev.data_ptr(), dh.data_ptr(),
+                                         dc_next.data_ptr(), dgates.data_ptr(), dc_prev.data_ptr(),
+                                         B, H, _lut_arg(lut), _stream_handle(stream))
     if st != 0:
-        raise KtanhError(st, "klstm_cell_backward")
+        raise KtanhError(st, _entry)
     return dgates, dc_prev

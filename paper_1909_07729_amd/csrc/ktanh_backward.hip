@@ -64,7 +64,7 @@ __device__ __forceinline__ float gelu_argument(float x)
 
 // One 32-bit word of each stream: a packed BFloat16 pair (ELEM = uint16_t) or one Float32
 // (ELEM = uint32_t).  A single BFloat16 element travels in the low half of the word.
-template <class ELEM, int GRAD>
+template <class ELEM, int GRAD, bool WIDE>
 __device__ __forceinline__ uint32_t grad_word(uint32_t dy_w, uint32_t v_w, const LaneTable &tab)
 {
     if constexpr (sizeof(ELEM) == 2) {
@@ -72,9 +72,9 @@ __device__ __forceinline__ uint32_t grad_word(uint32_t dy_w, uint32_t v_w, const
         const float v[2] = {widen_lo(v_w), widen_hi(v_w)};
         float k[2] = {0.f, 0.f};
         if constexpr (GRAD == GRAD_SWISH) {
-            ksigmoid_f32_pair<true, false>(v_w, tab, k[0], k[1]);
+            ksigmoid_f32_pair<true, WIDE>(v_w, tab, k[0], k[1]);
         } else if constexpr (GRAD == GRAD_GELU) {
-            const uint32_t t2 = ktanh_pair<true, false>(narrow_pair(gelu_argument(v[0]), gelu_argument(v[1])), tab);
+            const uint32_t t2 = ktanh_pair<true, WIDE>(narrow_pair(gelu_argument(v[0]), gelu_argument(v[1])), tab);
             k[0] = widen_lo(t2);
             k[1] = widen_hi(t2);
         }
@@ -84,10 +84,10 @@ __device__ __forceinline__ uint32_t grad_word(uint32_t dy_w, uint32_t v_w, const
         float k = 0.f;
         if constexpr (GRAD == GRAD_SWISH) {
             // 0.5 * t is exact for every K output t that can change the sum, so the multiply-add may fuse
-            const float t = __uint_as_float(ktanh_f32_one(__float_as_uint(0.5f * v), tab));
+            const float t = __uint_as_float(ktanh_f32_one<WIDE>(__float_as_uint(0.5f * v), tab));
             k = __builtin_fmaf(0.5f, t, 0.5f);
         } else if constexpr (GRAD == GRAD_GELU) {
-            k = __uint_as_float(ktanh_f32_one(__float_as_uint(gelu_argument(v)), tab));
+            k = __uint_as_float(ktanh_f32_one<WIDE>(__float_as_uint(gelu_argument(v)), tab));
         }
         return __float_as_uint(dy * slope_of<GRAD>(v, k));
     }
@@ -100,23 +100,29 @@ __device__ __forceinline__ uint32_t grad_word(uint32_t dy_w, uint32_t v_w, const
 // body (n_edge < 64 of them) are taken by block 0.  IN_UNALIGNED: an input disagrees with `dx`
 // modulo 16 bytes, so both are read with 16-byte loads from element-aligned addresses.  The table
 // reads of Swish and GELU need every lane enabled, so bounds predicate only the loads and stores.
+// The arguments a wavefront needs before its loads (the three body pointers, nvec, skew, n_edge)
+// come first, as scalars: the leading scalar arguments of a kernel arrive preloaded in registers.
 template <class ELEM>
-struct GradArgs {
+struct GradEdge {
     const ELEM *dy, *v;  // the whole tensors
     ELEM *dx;
-    unsigned long long n, nvec;
-    unsigned n_head, n_edge, skew;
+    unsigned long long n;
+    unsigned n_head;
 };
 
-template <class ELEM, int GRAD, bool IN_UNALIGNED>
-__global__ __launch_bounds__(kBlock) void grad_stream_kernel(GradArgs<ELEM> g, KtLutPack pack)
+template <class ELEM, int GRAD, bool WIDE, bool IN_UNALIGNED>
+__global__ __launch_bounds__(kBlock) void grad_stream_kernel(const char *bdy0, const char *bv0,
+                                                             uint4 *bdx0,  // the aligned bodies
+                                                             unsigned long long nvec, unsigned skew,
+                                                             unsigned n_edge, GradEdge<ELEM> g,
+                                                             KtLutPack pack)
 {
     const LaneTable tab(pack);
     const unsigned long long slot = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
-    const unsigned long long at = slot - g.skew;
-    const bool live = slot >= g.skew && at < g.nvec;
-    const char *bdy = reinterpret_cast<const char *>(g.dy + g.n_head) + 16 * at;
-    const char *bv = reinterpret_cast<const char *>(g.v + g.n_head) + 16 * at;
+    const unsigned long long at = slot - skew;
+    const bool live = slot >= skew && at < nvec;
+    const char *bdy = bdy0 + 16 * at;
+    const char *bv = bv0 + 16 * at;
     uint4 a = uint4{0u, 0u, 0u, 0u}, b = uint4{0u, 0u, 0u, 0u};
     if (live) {
         if constexpr (IN_UNALIGNED) {
@@ -127,24 +133,33 @@ __global__ __launch_bounds__(kBlock) void grad_stream_kernel(GradArgs<ELEM> g, K
             b = load_stream(reinterpret_cast<const uint4 *>(bv));
         }
     }
-    const uint4 r = uint4{grad_word<ELEM, GRAD>(a.x, b.x, tab), grad_word<ELEM, GRAD>(a.y, b.y, tab),
-                          grad_word<ELEM, GRAD>(a.z, b.z, tab), grad_word<ELEM, GRAD>(a.w, b.w, tab)};
-    if (live) store_stream(reinterpret_cast<uint4 *>(g.dx + g.n_head) + at, r);
-    if (g.n_edge != 0 && blockIdx.x == 0) {  // uniform over the block
+    const uint4 r = uint4{grad_word<ELEM, GRAD, WIDE>(a.x, b.x, tab), grad_word<ELEM, GRAD, WIDE>(a.y, b.y, tab),
+                          grad_word<ELEM, GRAD, WIDE>(a.z, b.z, tab), grad_word<ELEM, GRAD, WIDE>(a.w, b.w, tab)};
+    if (live) store_stream(bdx0 + at, r);
+    if (n_edge != 0 && blockIdx.x == 0) {  // uniform over the block
         const unsigned k = threadIdx.x;
-        const bool some = k < g.n_edge;
-        const unsigned long long i = k < g.n_head ? k : g.n - g.n_edge + k;
+        const bool some = k < n_edge;
+        const unsigned long long i = k < g.n_head ? k : g.n - n_edge + k;
         const uint32_t d1 = some ? g.dy[i] : 0u, v1 = some ? g.v[i] : 0u;
-        const uint32_t r1 = grad_word<ELEM, GRAD>(d1, v1, tab);
+        const uint32_t r1 = grad_word<ELEM, GRAD, WIDE>(d1, v1, tab);
         if (some) g.dx[i] = (ELEM)r1;
     }
 }
 
+ktanh_status_t pack_grad(const ktanh_lut_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut_f32(lut, pack) : kt_pack_lut_bf16(lut, pack);
+}
+ktanh_status_t pack_grad(const ktanh_lut64_t *lut, bool f32, KtLutPack *pack)
+{
+    return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
+}
 // `lut` is only read by Swish and GELU; TanH and Sigmoid pass NULL and Table 1 rides along unused.
-template <class ELEM, int GRAD>
-ktanh_status_t launch_grad(const void *dy, const void *v, void *dx, size_t n, const ktanh_lut_t *lut,
+template <class ELEM, int GRAD, class Lut>
+ktanh_status_t launch_grad(const void *dy, const void *v, void *dx, size_t n, const Lut *lut,
                            ktanh_stream_t stream)
 {
+    constexpr bool WIDE = is_wide(static_cast<const Lut *>(nullptr));
     constexpr size_t kPerVec = 16 / sizeof(ELEM);
     if (n == 0) return KT_OK;
     if (dy == nullptr || v == nullptr || dx == nullptr) return KT_ERR_NULL;
@@ -153,25 +168,30 @@ ktanh_status_t launch_grad(const void *dy, const void *v, void *dx, size_t n, co
     if ((ady | av | adx) & (sizeof(ELEM) - 1)) return KT_ERR_ALIGN;
     if (n > (size_t)1 << 40) return KT_ERR_SHAPE;
     KtLutPack pack;
-    const ktanh_status_t st = sizeof(ELEM) == 2 ? kt_pack_lut_bf16(lut, &pack) : kt_pack_lut_f32(lut, &pack);
+    const ktanh_status_t st = pack_grad(lut, sizeof(ELEM) == 4, &pack);
     if (st != KT_OK) return st;
-    GradArgs<ELEM> g;
+    GradEdge<ELEM> g;
     g.dy = static_cast<const ELEM *>(dy);
     g.v = static_cast<const ELEM *>(v);
     g.dx = static_cast<ELEM *>(dx);
     g.n = n;
     size_t head = ((16 - (adx & 15)) & 15) / sizeof(ELEM);
     if (head > n) head = n;
-    g.nvec = (n - head) / kPerVec;
+    const size_t nvec = (n - head) / kPerVec;
     g.n_head = (unsigned)head;
-    g.n_edge = (unsigned)(n - g.nvec * kPerVec);
-    g.skew = (unsigned)((reinterpret_cast<uintptr_t>(g.dx + head) / 16) % kBlock);
-    size_t tiles = (g.nvec + g.skew + kBlock - 1) / kBlock;
+    const unsigned n_edge = (unsigned)(n - nvec * kPerVec);
+    const unsigned skew = (unsigned)((reinterpret_cast<uintptr_t>(g.dx + head) / 16) % kBlock);
+    size_t tiles = (nvec + skew + kBlock - 1) / kBlock;
     if (tiles == 0) tiles = 1;  // edge elements only
-    if (tiles > 0x7FFFFFFFull) return KT_ERR_SHAPE;
+    if (tiles > kMaxTiles) return KT_ERR_SHAPE;
+    const char *bdy = reinterpret_cast<const char *>(g.dy + head);
+    const char *bv = reinterpret_cast<const char *>(g.v + head);
+    uint4 *bdx = reinterpret_cast<uint4 *>(g.dx + head);
     if ((ady & 15) == (adx & 15) && (av & 15) == (adx & 15))
-        return launch_checked(grad_stream_kernel<ELEM, GRAD, false>, (unsigned)tiles, kBlock, stream, g, pack);
-    return launch_checked(grad_stream_kernel<ELEM, GRAD, true>, (unsigned)tiles, kBlock, stream, g, pack);
+        return launch_checked(grad_stream_kernel<ELEM, GRAD, WIDE, false>, (unsigned)tiles, kBlock, stream,
+                              bdy, bv, bdx, (unsigned long long)nvec, skew, n_edge, g, pack);
+    return launch_checked(grad_stream_kernel<ELEM, GRAD, WIDE, true>, (unsigned)tiles, kBlock, stream, bdy,
+                          bv, bdx, (unsigned long long)nvec, skew, n_edge, g, pack);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -180,6 +200,7 @@ ktanh_status_t launch_grad(const void *dy, const void *v, void *dx, size_t n, co
 // table reads need every lane enabled, so bounds predicate only the memory accesses.
 constexpr int kCellBlock = 256;
 
+template <bool WIDE>
 __global__ __launch_bounds__(kCellBlock) void lstm_cell_backward_kernel(
     const uint32_t *__restrict__ gates, const float2 *__restrict__ c_prev,
     const uint32_t *__restrict__ dh, const float2 *dc_next, uint32_t *__restrict__ dgates,
@@ -205,10 +226,10 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_backward_kernel(
     }
 
     float ig[2], fg[2], og[2];
-    ksigmoid_f32_pair(wi, tab, ig[0], ig[1]);
-    ksigmoid_f32_pair(wf, tab, fg[0], fg[1]);
-    ksigmoid_f32_pair(wo, tab, og[0], og[1]);
-    const uint32_t g2 = ktanh_pair(wg, tab);
+    ksigmoid_f32_pair<true, WIDE>(wi, tab, ig[0], ig[1]);
+    ksigmoid_f32_pair<true, WIDE>(wf, tab, fg[0], fg[1]);
+    ksigmoid_f32_pair<true, WIDE>(wo, tab, og[0], og[1]);
+    const uint32_t g2 = ktanh_pair<true, WIDE>(wg, tab);
     const float gg[2] = {widen_lo(g2), widen_hi(g2)};
     const float cp[2] = {c0.x, c0.y};
     float c1[2];
@@ -217,7 +238,7 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_backward_kernel(
         const float keep = fg[k] * cp[k], add = ig[k] * gg[k];
         c1[k] = keep + add;
     }
-    const uint32_t tc2 = ktanh_pair(narrow_pair(c1[0], c1[1]), tab);
+    const uint32_t tc2 = ktanh_pair<true, WIDE>(narrow_pair(c1[0], c1[1]), tab);
     const float tc[2] = {widen_lo(tc2), widen_hi(tc2)};
     const float dhv[2] = {widen_lo(wdh), widen_hi(wdh)};
     const float dnx[2] = {dcn.x, dcn.y};
@@ -256,13 +277,13 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_backward_kernel(
 extern "C" ktanh_status_t ktanh_bf16_backward(const uint16_t *dy, const uint16_t *y, uint16_t *dx,
                                               size_t n, ktanh_stream_t stream)
 {
-    return launch_grad<uint16_t, GRAD_TANH>(dy, y, dx, n, nullptr, stream);
+    return launch_grad<uint16_t, GRAD_TANH>(dy, y, dx, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
 }
 
 extern "C" ktanh_status_t ksigmoid_backward(const uint16_t *dy, const uint16_t *s, uint16_t *dx,
                                             size_t n, ktanh_stream_t stream)
 {
-    return launch_grad<uint16_t, GRAD_SIGMOID>(dy, s, dx, n, nullptr, stream);
+    return launch_grad<uint16_t, GRAD_SIGMOID>(dy, s, dx, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
 }
 
 extern "C" ktanh_status_t kswish_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
@@ -280,13 +301,13 @@ extern "C" ktanh_status_t kgelu_backward(const uint16_t *dy, const uint16_t *x, 
 extern "C" ktanh_status_t ktanh_f32_backward(const float *dy, const float *y, float *dx, size_t n,
                                              ktanh_stream_t stream)
 {
-    return launch_grad<uint32_t, GRAD_TANH>(dy, y, dx, n, nullptr, stream);
+    return launch_grad<uint32_t, GRAD_TANH>(dy, y, dx, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
 }
 
 extern "C" ktanh_status_t ksigmoid_f32_backward(const float *dy, const float *s, float *dx, size_t n,
                                                 ktanh_stream_t stream)
 {
-    return launch_grad<uint32_t, GRAD_SIGMOID>(dy, s, dx, n, nullptr, stream);
+    return launch_grad<uint32_t, GRAD_SIGMOID>(dy, s, dx, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
 }
 
 extern "C" ktanh_status_t kswish_f32_backward(const float *dy, const float *x, float *dx, size_t n,
@@ -301,32 +322,83 @@ extern "C" ktanh_status_t kgelu_f32_backward(const float *dy, const float *x, fl
     return launch_grad<uint32_t, GRAD_GELU>(dy, x, dx, n, lut, stream);
 }
 
-extern "C" ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev,
-                                              const uint16_t *dh, const float *dc_next,
-                                              uint16_t *dgates, float *dc_prev, size_t B, size_t H,
-                                              const ktanh_lut_t *lut, ktanh_stream_t stream)
+namespace {
+
+ktanh_status_t pack_cell(const ktanh_lut_t *lut, KtLutPack *pack) { return kt_pack_lut_bf16(lut, pack); }
+ktanh_status_t pack_cell(const ktanh_lut64_t *lut, KtLutPack *pack) { return kt_pack_lut64_bf16(lut, pack); }
+
+template <class Lut>
+ktanh_status_t launch_cell_backward(const uint16_t *gates, const float *c_prev, const uint16_t *dh,
+                                    const float *dc_next, uint16_t *dgates, float *dc_prev, size_t B,
+                                    size_t H, const Lut *lut, ktanh_stream_t stream)
 {
+    constexpr bool WIDE = is_wide(static_cast<const Lut *>(nullptr));
     if (B == 0 || H == 0) return KT_OK;
     if (gates == nullptr || c_prev == nullptr || dh == nullptr || dc_next == nullptr ||
         dgates == nullptr || dc_prev == nullptr)
         return KT_ERR_NULL;
     if (H % 8 != 0) return KT_ERR_SHAPE;
     if (B > ((size_t)1 << 40) || H > ((size_t)1 << 40)) return KT_ERR_SHAPE;
-    const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_prev) |
-                          reinterpret_cast<uintptr_t>(dh) | reinterpret_cast<uintptr_t>(dc_next) |
-                          reinterpret_cast<uintptr_t>(dgates) | reinterpret_cast<uintptr_t>(dc_prev);
-    if (mis & 15) return KT_ERR_ALIGN;
+    // the kernel moves BFloat16 pairs (4 bytes) and Float32 pairs (8 bytes)
+    const uintptr_t words = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(dh) |
+                            reinterpret_cast<uintptr_t>(dgates);
+    const uintptr_t states = reinterpret_cast<uintptr_t>(c_prev) | reinterpret_cast<uintptr_t>(dc_next) |
+                             reinterpret_cast<uintptr_t>(dc_prev);
+    if ((words & 3) || (states & 7)) return KT_ERR_ALIGN;
     KtLutPack pack;
-    const ktanh_status_t st = kt_pack_lut_bf16(lut, &pack);
+    const ktanh_status_t st = pack_cell(lut, &pack);
     if (st != KT_OK) return st;
+    if (B > (1ull << 28) / (H / 2)) return KT_ERR_SHAPE;
     const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
     if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // word indices inside [B][4H] fit 32 bits
     const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
-    return launch_checked(lstm_cell_backward_kernel, (unsigned)blocks, kCellBlock, stream,
+    return launch_checked(lstm_cell_backward_kernel<WIDE>, (unsigned)blocks, kCellBlock, stream,
                           reinterpret_cast<const uint32_t *>(gates),
                           reinterpret_cast<const float2 *>(c_prev),
                           reinterpret_cast<const uint32_t *>(dh),
                           reinterpret_cast<const float2 *>(dc_next),
                           reinterpret_cast<uint32_t *>(dgates), reinterpret_cast<float2 *>(dc_prev),
                           (unsigned)n_pairs, (unsigned)(H / 2), pack);
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev,
+                                              const uint16_t *dh, const float *dc_next,
+                                              uint16_t *dgates, float *dc_prev, size_t B, size_t H,
+                                              const ktanh_lut_t *lut, ktanh_stream_t stream)
+{
+    return launch_cell_backward(gates, c_prev, dh, dc_next, dgates, dc_prev, B, H, lut, stream);
+}
+
+extern "C" ktanh_status_t klstm_cell64_backward(const uint16_t *gates, const float *c_prev,
+                                                const uint16_t *dh, const float *dc_next,
+                                                uint16_t *dgates, float *dc_prev, size_t B, size_t H,
+                                                const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_cell_backward(gates, c_prev, dh, dc_next, dgates, dc_prev, B, H, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
+                                            size_t n, const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad<uint16_t, GRAD_SWISH>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu64_backward(const uint16_t *dy, const uint16_t *x, uint16_t *dx,
+                                           size_t n, const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad<uint16_t, GRAD_GELU>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kswish64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                                const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad<uint32_t, GRAD_SWISH>(dy, x, dx, n, lut, stream);
+}
+
+extern "C" ktanh_status_t kgelu64_f32_backward(const float *dy, const float *x, float *dx, size_t n,
+                                               const ktanh_lut64_t *lut, ktanh_stream_t stream)
+{
+    return launch_grad<uint32_t, GRAD_GELU>(dy, x, dx, n, lut, stream);
 }

@@ -21,6 +21,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBlock = 64;  // one wavefront per block: a finished wavefront's slot is refilled at once
+// A launch holds fewer than 2^32 work-items: at most this many single-wavefront tiles (64 GiB of
+// 128-bit vectors).  Larger tensors are refused before anything is launched.
+constexpr unsigned long long kMaxTiles = (1ull << 26) - 1;
 constexpr uint32_t kMag2 = 0x7FFF7FFFu;
 
 __device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
@@ -225,10 +228,13 @@ __device__ __forceinline__ uint4 load_stream_unaligned(const void *p)
     __builtin_memcpy(&t, p, sizeof t);
     return uint4{t.x, t.y, t.z, t.w};
 }
+// The two idle issue slots after the store belong to it: a store of more than 64 bits reads its
+// data registers for a few cycles after issue, and the compiler, which cannot see into the
+// statement, may otherwise let the very next instruction overwrite them.
 __device__ __forceinline__ void store_stream(uint4 *p, uint4 v)
 {
     const u32x4 t = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(t) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1" : : "v"(p), "v"(t) : "memory");
 }
 // One dword at `base` (uniform) + `byte_offset` (per lane).
 __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offset, uint32_t v)
@@ -310,6 +316,10 @@ __device__ __forceinline__ uint4 apply_vec_f32(uint4 v, const LaneTable &tab)
     return uint4{apply_f32_one<OP, WIDE>(v.x, tab), apply_f32_one<OP, WIDE>(v.y, tab),
                  apply_f32_one<OP, WIDE>(v.z, tab), apply_f32_one<OP, WIDE>(v.w, tab)};
 }
+
+// Which table layout a caller's table type selects.
+constexpr bool is_wide(const ktanh_lut_t *) { return false; }
+constexpr bool is_wide(const ktanh_lut64_t *) { return true; }
 
 // Enqueues `kernel` and returns the status of this very launch (the launch macro would only leave it
 // in the runtime's last-error slot, next to whatever an earlier, unrelated call left there).

@@ -193,20 +193,21 @@ ktanh_status_t launch_cell(const uint16_t *gates, const float *c_in, float *c_ou
     if (gates == nullptr || c_in == nullptr || c_out == nullptr || h_out == nullptr)
         return KT_ERR_NULL;
     if (H % 8 != 0) return KT_ERR_SHAPE;
-    // sizes: T*B*4H elements must stay far below 2^63, T and H/8 must fit 32 bits
-    if (T > 0x7FFFFFFFull || H / 2 > 0xFFFFFFFFull || B > ((size_t)1 << 40) ||
-        (B * (H / 8)) > ((size_t)1 << 40) / T)
+    // one time step holds fewer than 2^28 lane pairs (byte offsets inside a step fit 32 bits), and
+    // T*B*4H elements stay far below 2^63; every bound is tested by division, so nothing wraps
+    if (T > 0x7FFFFFFFull || B >= ((size_t)1 << 28) || H >= ((size_t)1 << 29) ||
+        B > (((size_t)1 << 28) - 1) / (H / 2))
         return KT_ERR_SHAPE;
-    const uintptr_t mis = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(c_in) |
-                          reinterpret_cast<uintptr_t>(c_out) | reinterpret_cast<uintptr_t>(h_out);
-    if (mis & 15) return KT_ERR_ALIGN;
+    // the kernel moves BFloat16 pairs (4 bytes) and Float32 pairs (8 bytes)
+    const uintptr_t words = reinterpret_cast<uintptr_t>(gates) | reinterpret_cast<uintptr_t>(h_out);
+    const uintptr_t states = reinterpret_cast<uintptr_t>(c_in) | reinterpret_cast<uintptr_t>(c_out);
+    if ((words & 3) || (states & 7)) return KT_ERR_ALIGN;
     KtLutPack pack;
     bool within_unit = true;
     const ktanh_status_t st = pack_cell(lut, &pack, &within_unit);
     if (st != KT_OK) return st;
 
-    const unsigned long long n_pairs = (unsigned long long)B * (H / 2);
-    if (n_pairs >= (1ull << 28)) return KT_ERR_SHAPE;  // byte offsets inside one step fit 32 bits
+    const unsigned long long n_pairs = (unsigned long long)B * (H / 2);  // < 2^28, checked above
     const unsigned long long blocks = (n_pairs + kCellBlock - 1) / kCellBlock;
     return launch_checked(lstm_cell_kernel<WIDE>, (unsigned)blocks, kCellBlock, stream,
                           reinterpret_cast<const uint32_t *>(gates),

@@ -1,0 +1,69 @@
+// libktanh_probe: measurement yardsticks, not operations of the paper.  Each is the launch of the
+// element-wise entry points (one wavefront per block, one 128-bit vector per lane, the same load and
+// store policies) with the arithmetic, the stores or the loads taken out, so that a benchmark can
+// put what the memory system allows for this launch shape next to the K-TanH figures.
+#include "ktanh_probe.h"
+#include "ktanh_stream_impl.h"
+
+using namespace ktanh_device;
+
+namespace {
+
+// Loads only: the store is kept in the code behind a test no benchmark tensor passes, so that the
+// loads stay; if it ever fires it writes inside `sink` (1 KiB, one vector per lane).
+__global__ __launch_bounds__(kBlock) void read_kernel(const uint4 *__restrict__ vin, uint4 *sink,
+                                                      unsigned long long nvec)
+{
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    if (at >= nvec) return;
+    const uint4 v = load_stream(vin + at);
+    if ((v.x ^ v.y) == 0x7FC1A5A5u && (v.z ^ v.w) == 0x5A5A1CF7u) store_stream(sink + threadIdx.x, v);
+}
+
+// Stores only: a fixed pattern.
+__global__ __launch_bounds__(kBlock) void write_kernel(uint4 *__restrict__ vout, unsigned long long nvec)
+{
+    const unsigned long long at = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    if (at >= nvec) return;
+    store_stream(vout + at, uint4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
+}
+
+ktanh_status_t check(const void *p, size_t n_bytes, unsigned long long *tiles)
+{
+    if (p == nullptr) return KT_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(p) % 1024 != 0) return KT_ERR_ALIGN;
+    if (n_bytes % 16 != 0) return KT_ERR_SHAPE;
+    *tiles = (n_bytes / 16 + kBlock - 1) / kBlock;
+    return *tiles > kMaxTiles ? KT_ERR_SHAPE : KT_OK;
+}
+
+}  // namespace
+
+extern "C" ktanh_status_t ktanh_probe_copy(const uint16_t *in, uint16_t *out, size_t n,
+                                           ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_COPY>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
+}
+
+extern "C" ktanh_status_t ktanh_probe_read(const void *in, void *sink, size_t n_bytes,
+                                           ktanh_stream_t stream)
+{
+    if (n_bytes == 0) return KT_OK;
+    unsigned long long tiles = 0;
+    const ktanh_status_t st = check(in, n_bytes, &tiles);
+    if (st != KT_OK) return st;
+    if (sink == nullptr) return KT_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(sink) % 16 != 0) return KT_ERR_ALIGN;
+    return launch_checked(read_kernel, (unsigned)tiles, kBlock, stream, static_cast<const uint4 *>(in),
+                          static_cast<uint4 *>(sink), (unsigned long long)(n_bytes / 16));
+}
+
+extern "C" ktanh_status_t ktanh_probe_write(void *out, size_t n_bytes, ktanh_stream_t stream)
+{
+    if (n_bytes == 0) return KT_OK;
+    unsigned long long tiles = 0;
+    const ktanh_status_t st = check(out, n_bytes, &tiles);
+    if (st != KT_OK) return st;
+    return launch_checked(write_kernel, (unsigned)tiles, kBlock, stream, static_cast<uint4 *>(out),
+                          (unsigned long long)(n_bytes / 16));
+}

@@ -1,0 +1,67 @@
+"""Python front-end of ``libktanh_probe.so`` (``include/ktanh_probe.h``): the measurement yardsticks
+the benchmark puts next to the K-TanH figures.  Marshalling only; not part of the product path."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from .binding import KtanhError, _BF16_VIEWS, _check, _stream_handle
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libktanh_probe.so")
+SIGNATURES = {"ktanh_probe_copy": "ppns", "ktanh_probe_read": "ppns", "ktanh_probe_write": "pns"}
+EXPORTS = tuple(SIGNATURES)
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        kinds = {"p": ctypes.c_void_p, "n": ctypes.c_size_t, "s": ctypes.c_void_p}
+        for name, params in SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.argtypes = [kinds[k] for k in params]
+            fn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def ktanh_probe_copy(x, out, stream=None):
+    """Copies a 16-bit tensor with the launch of ``ktanh_bf16`` and no arithmetic."""
+    _check(x, _BF16_VIEWS, "in")
+    _check(out, _BF16_VIEWS, "out")
+    if out.numel() != x.numel():
+        raise ValueError("in and out differ in size")
+    st = load_library().ktanh_probe_copy(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_probe_copy")
+    return out
+
+
+def ktanh_probe_read(x: torch.Tensor, sink: torch.Tensor, stream=None):
+    """The loads of that launch alone over the bytes of ``x``; ``sink`` is 1 KiB of device scratch."""
+    if not (x.is_cuda and sink.is_cuda and x.is_contiguous() and sink.is_contiguous()):
+        raise ValueError("x and sink must be contiguous CUDA tensors")
+    if sink.numel() * sink.element_size() < 1024:
+        raise ValueError("sink must hold 1 KiB")
+    st = load_library().ktanh_probe_read(x.data_ptr(), sink.data_ptr(), x.numel() * x.element_size(),
+                                         _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_probe_read")
+
+
+def ktanh_probe_write(out: torch.Tensor, stream=None):
+    """The stores of that launch alone over the bytes of ``out``."""
+    if not (out.is_cuda and out.is_contiguous()):
+        raise ValueError("out must be a contiguous CUDA tensor")
+    st = load_library().ktanh_probe_write(out.data_ptr(), out.numel() * out.element_size(),
+                                          _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_probe_write")

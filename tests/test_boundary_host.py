@@ -20,18 +20,74 @@ def binding():
     return b
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "ktanh.h")).read()
+def _declarations(header):
+    """{function name: number of parameters} for every function a header declares."""
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(k\w+)\s*\(", text)))
+    found = {}
+    for name, params in re.findall(r"\b(k\w+)\s*\(([^)]*)\)\s*;", text):
+        params = params.strip()
+        found[name] = 0 if params in ("", "void") else params.count(",") + 1
+    return found
 
 
-def test_every_declared_symbol_is_exported(binding):
-    names = _declared_functions()
-    assert set(names) == set(binding.EXPORTS)
-    lib = binding.load_library()
-    for name in names:
-        assert getattr(lib, name) is not None
+@pytest.fixture(scope="module")
+def probe(binding):
+    from paper_1909_07729_amd import probe as p
+    if not os.path.exists(p.LIB_PATH):
+        from paper_1909_07729_amd import build
+        build.build_probe_library()
+    p.load_library()
+    return p
+
+
+def test_every_declared_symbol_is_exported(binding, probe):
+    for module, header in ((binding, "ktanh.h"), (probe, "ktanh_probe.h")):
+        declared = _declarations(header)
+        assert set(declared) == set(module.EXPORTS), header
+        lib = module.load_library()
+        for name in declared:
+            assert getattr(lib, name) is not None
+    # the yardsticks stay out of the product library
+    assert not any(hasattr(binding.load_library(), name) for name in probe.EXPORTS)
+
+
+def test_prototypes_match_the_header(binding, probe):
+    """Every ctypes prototype has as many parameters as the header's declaration, and pointer, size and
+    table kinds where the header has them."""
+    for module, header in ((binding, "ktanh.h"), (probe, "ktanh_probe.h")):
+        lib = module.load_library()
+        for name, count in _declarations(header).items():
+            fn = getattr(lib, name)
+            assert len(fn.argtypes) == count == len(module.SIGNATURES[name]), name
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "ktanh.h")).read(), flags=re.S)
+    for name, params in re.findall(r"\b(k\w+)\s*\(([^)]*)\)\s*;", text):
+        kinds = binding.SIGNATURES[name]
+        for kind, param in zip(kinds, [q.strip() for q in params.split(",")] if params.strip() not in ("", "void") else []):
+            if kind == "l":
+                assert "ktanh_lut_t" in param, (name, param)
+            elif kind == "L":
+                assert "ktanh_lut64_t" in param, (name, param)
+            elif kind == "n":
+                assert param.startswith("size_t"), (name, param)
+            elif kind == "s":
+                assert param.startswith("ktanh_stream_t"), (name, param)
+            elif kind == "p":
+                assert "*" in param and "lut" not in param, (name, param)
+
+
+def test_a_failed_call_raises_ktanh_error(binding, monkeypatch):
+    """The error path of the table fits: a non-zero status becomes a KtanhError that names the call."""
+    class Failing:
+        def __getattr__(self, name):
+            if name == "ktanh_status_string":
+                return lambda status: b"KT_ERR_NULL: a required pointer is NULL"
+            return lambda *args: 1
+    monkeypatch.setattr(binding, "_lib", Failing())
+    for name in ("ktanh_fit_lut", "ktanh_fit_lut_bmin0", "ktanh_fit_lut64"):
+        with pytest.raises(binding.KtanhError) as err:
+            getattr(binding, name)()
+        assert err.value.status == 1 and name in str(err.value)
 
 
 def test_struct_layout_is_96_bytes(binding):
@@ -81,7 +137,10 @@ def test_argument_errors_are_returned_before_any_launch(binding):
     assert lib.klstm_cell(null, null, null, null, 0, 4, 8, None, null) == 0
     assert lib.klstm_cell(null, fake, fake, fake, 1, 4, 8, None, null) == 1
     assert lib.klstm_cell(fake, fake, fake, fake, 1, 4, 12, None, null) == 4
-    assert lib.klstm_cell(ctypes.c_void_p(0x1008), fake, fake, fake, 1, 4, 8, None, null) == 2
+    # BFloat16 pairs need 4-byte alignment, Float32 pairs 8-byte alignment; nothing more
+    assert lib.klstm_cell(ctypes.c_void_p(0x1002), fake, fake, fake, 1, 4, 8, None, null) == 2
+    assert lib.klstm_cell(fake, ctypes.c_void_p(0x1004), fake, fake, 1, 4, 8, None, null) == 2
+    assert lib.klstm_cell(fake, fake, fake, ctypes.c_void_p(0x1006), 1, 4, 8, None, null) == 2
     assert lib.klstm_cell(fake, fake, fake, fake, 1, 4, 8, ctypes.byref(bad), null) == 3
     assert b"KT_ERR_LUT" in lib.ktanh_status_string(3)
 
@@ -159,15 +218,19 @@ def test_host_sources_under_address_and_ub_sanitizers(tmp_path):
 
 
 def test_sizes_beyond_the_grid_limit_are_rejected_on_the_host(binding):
-    """A grid holds at most 2^31 - 1 single-wavefront blocks; larger tensors are refused (status 4)
-    before anything is launched, so fake pointers are never touched."""
+    """A launch holds fewer than 2^32 work-items, i.e. at most 2^26 - 1 single-wavefront tiles of
+    1 KiB of output; larger tensors are refused (status 4) before anything is launched, so the fake
+    pointers are never touched."""
     lib = binding.load_library()
     fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
     for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "ktanh64_bf16"):
         assert getattr(lib, name)(fake, fake, (1 << 40) + 8, None, null) == 4
-        assert getattr(lib, name)(fake, fake, 1 << 40, None, null) == 4      # 2^31 blocks: one too many
-    for name in ("ktanh_f32", "ksigmoid_f32", "ktanh_f32_to_bf16", "ktanh64_f32"):
-        assert getattr(lib, name)(fake, fake, 1 << 39, None, null) == 4
+        assert getattr(lib, name)(fake, fake, 1 << 35, None, null) == 4      # 2^26 tiles: one too many
+    for name in ("ktanh_f32", "ksigmoid_f32", "ktanh64_f32"):
+        assert getattr(lib, name)(fake, fake, 1 << 34, None, null) == 4
+    assert lib.ktanh_f32_to_bf16(fake, fake, 1 << 34, None, null) == 4       # 512-byte tiles of output
+    for name in ("ktanh_bf16_backward", "ksigmoid_backward"):
+        assert getattr(lib, name)(fake, fake, fake, 1 << 35, null) == 4
     # LSTM cell: B * H / 2 lane pairs must stay below 2^28; T below 2^31
     assert lib.klstm_cell(fake, fake, fake, fake, 1, 1 << 20, 1 << 9, None, null) == 4
     assert lib.klstm_cell(fake, fake, fake, fake, 1 << 31, 1, 8, None, null) == 4
@@ -192,9 +255,6 @@ def test_gradient_entry_points_reject_bad_arguments(binding):
         assert fn(ctypes.c_void_p(0x1001), fake, fake, 8, None, null) == 2
         assert fn(fake, fake, fake, (1 << 40) + 8, None, null) == 4
         assert fn(fake, fake, fake, 8, ctypes.byref(bad), null) == 3
-    assert lib.ktanh_stream_copy(null, null, 0, null) == 0
-    assert lib.ktanh_stream_copy(fake, null, 8, null) == 1
-    assert lib.ktanh_stream_copy(ctypes.c_void_p(0x1001), fake, 8, null) == 2
     for name in ("ktanh_f32_backward", "ksigmoid_f32_backward"):
         fn = getattr(lib, name)
         assert fn(null, null, null, 0, null) == 0
@@ -211,5 +271,31 @@ def test_gradient_entry_points_reject_bad_arguments(binding):
     assert bw(null, null, null, null, null, null, 0, 8, None, null) == 0
     assert bw(fake, fake, fake, null, fake, fake, 2, 8, None, null) == 1
     assert bw(fake, fake, fake, fake, fake, fake, 2, 12, None, null) == 4
-    assert bw(fake, fake, ctypes.c_void_p(0x1008), fake, fake, fake, 2, 8, None, null) == 2
+    assert bw(fake, fake, ctypes.c_void_p(0x1002), fake, fake, fake, 2, 8, None, null) == 2
+    assert bw(fake, ctypes.c_void_p(0x1004), fake, fake, fake, fake, 2, 8, None, null) == 2
     assert bw(fake, fake, fake, fake, fake, fake, 1 << 20, 1 << 9, None, null) == 4
+    bad64 = binding.KtanhLut64.from_tuples([(126, 9, 0)] * 64)
+    for name in ("kswish64_backward", "kgelu64_backward", "kswish64_f32_backward", "kgelu64_f32_backward"):
+        fn = getattr(lib, name)
+        assert fn(null, null, null, 0, None, null) == 0
+        assert fn(fake, fake, null, 8, None, null) == 1
+        assert fn(ctypes.c_void_p(0x1001), fake, fake, 8, None, null) == 2
+        assert fn(fake, fake, fake, 8, ctypes.byref(bad64), null) == 3
+    bw64 = lib.klstm_cell64_backward
+    assert bw64(null, null, null, null, null, null, 0, 8, None, null) == 0
+    assert bw64(fake, fake, fake, null, fake, fake, 2, 8, None, null) == 1
+    assert bw64(fake, fake, fake, fake, fake, fake, 2, 12, None, null) == 4
+    assert bw64(fake, fake, fake, fake, fake, fake, 2, 8, ctypes.byref(bad64), null) == 3
+
+
+def test_probe_library_rejects_bad_arguments(probe):
+    lib = probe.load_library()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    aligned = ctypes.c_void_p(0x10000)
+    assert lib.ktanh_probe_copy(null, null, 0, null) == 0
+    assert lib.ktanh_probe_copy(fake, null, 8, null) == 1
+    assert lib.ktanh_probe_copy(ctypes.c_void_p(0x1001), fake, 8, null) == 2
+    assert lib.ktanh_probe_read(null, fake, 1024, null) == 1 and lib.ktanh_probe_read(aligned, null, 1024, null) == 1
+    assert lib.ktanh_probe_read(ctypes.c_void_p(0x1010), fake, 1024, null) == 2 and lib.ktanh_probe_read(aligned, fake, 1000, null) == 4
+    assert lib.ktanh_probe_write(null, 1024, null) == 1 and lib.ktanh_probe_write(ctypes.c_void_p(0x1010), 1024, null) == 2
+    assert lib.ktanh_probe_write(aligned, 1 << 37, null) == 4 and lib.ktanh_probe_write(null, 0, null) == 0

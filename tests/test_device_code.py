@@ -9,7 +9,7 @@ import pytest
 
 from paper_1909_07729_amd import build
 
-HIP_SOURCES = [s for s in build.SOURCES if s.endswith(".hip")]
+HIP_SOURCES = [s for s in build.SOURCES + build.PROBE_SOURCES if s.endswith(".hip")]
 
 
 @pytest.fixture(scope="module")
@@ -60,3 +60,24 @@ def test_lstm_steady_loop_waits_for_its_own_gate_words_only(assembly):
     text = assembly["ktanh_lstm.hip"]
     for count in (15, 14, 13, 12):
         assert f"s_waitcnt vmcnt({count})" in text, count
+
+
+def test_wide_stores_written_as_statements_keep_their_data_registers(assembly):
+    """A store of more than 64 bits reads its data registers for a few cycles after issue; the
+    compiler inserts the wait for stores it emits itself but cannot see into a statement, so each such
+    statement carries its own two idle slots."""
+    seen = 0
+    for src, text in assembly.items():
+        lines = text.splitlines()
+        for i, line in enumerate(lines):
+            if "global_store_dwordx4" in line and "sc0 sc1 nt" in line:
+                seen += 1
+                assert lines[i + 1].strip() == "s_nop 1", f"{src}: {line.strip()} is followed by {lines[i + 1].strip()}"
+    assert seen > 20
+
+
+def test_leading_scalar_arguments_are_preloaded(assembly):
+    """Every streaming kernel gets the pointers and sizes it needs for its first load in registers."""
+    for src in ("ktanh_stream.hip", "ktanh_backward.hip", "ktanh_probe.hip"):
+        lengths = [int(v) for v in re.findall(r"\.amdhsa_user_sgpr_kernarg_preload_length\s+(\d+)", assembly[src])]
+        assert lengths and min(lengths) >= 4, (src, sorted(set(lengths)))

@@ -310,21 +310,33 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
         assert np.array_equal(_to_host(hd, np.uint16), want_h), f"replay {replay}"
 
 
-def test_stream_copy_is_the_identity(gpu):
-    """ktanh_stream_copy moves bits unchanged (NaN payloads included), for any alignment, in place too."""
+def test_probe_yardsticks(gpu):
+    """The measurement library: ktanh_probe_copy moves bits unchanged (NaN payloads included) for any
+    alignment and in place; ktanh_probe_write fills exactly its range; ktanh_probe_read writes nothing."""
     binding, torch = gpu
+    from paper_1909_07729_amd import probe
     x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(100003, seed=73)])
     xd = _to_dev(torch, x)
-    assert np.array_equal(_to_host(binding.ktanh_stream_copy(xd), np.uint16), x)
+    assert np.array_equal(_to_host(probe.ktanh_probe_copy(xd, torch.empty_like(xd)), np.uint16), x)
     n = x.size - 16
     for off_in, off_out in ((0, 0), (1, 1), (3, 0), (0, 5), (7, 2)):
         outd = torch.full((x.size + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
-        binding.ktanh_stream_copy(xd[off_in:off_in + n], out=outd[8 + off_out:8 + off_out + n])
+        probe.ktanh_probe_copy(xd[off_in:off_in + n], outd[8 + off_out:8 + off_out + n])
         res = _to_host(outd, np.uint16)
         assert np.array_equal(res[8 + off_out:8 + off_out + n], x[off_in:off_in + n]), (off_in, off_out)
         assert np.all(res[:8 + off_out] == 0x5A5A) and np.all(res[8 + off_out + n:] == 0x5A5A)
-    binding.ktanh_stream_copy(xd, out=xd)
+    probe.ktanh_probe_copy(xd, xd)
     assert np.array_equal(_to_host(xd, np.uint16), x)
+    # write: 1 KiB-aligned start inside a guarded buffer, a length that ends inside a tile
+    buf = torch.full((4096 + 40000,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    start = (-buf.data_ptr() % 1024) // 2 + 512
+    probe.ktanh_probe_write(buf[start:start + 30008])
+    res = _to_host(buf, np.uint16)
+    assert np.all(res[start:start + 30008] == 0x3F80) and np.all(res[:start] == 0x5A5A) and np.all(res[start + 30008:] == 0x5A5A)
+    sink = torch.full((512,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    probe.ktanh_probe_read(buf[start:start + 30008], sink)
+    torch.cuda.synchronize()
+    assert np.all(_to_host(sink, np.uint16) == 0x5A5A) and np.array_equal(_to_host(buf, np.uint16), res)
 
 
 def test_graph_replay_of_the_later_entry_points(gpu, oracle):
@@ -759,6 +771,101 @@ def test_lstm_cell_backward(gpu, oracle, B, H):
     assert np.array_equal(dc.view(np.uint32)[~nanp], dc_ref.view(np.uint32)[~nanp])
 
 
+def test_gradients_on_64_interval_tables(gpu, oracle):
+    """kswish64_backward, kgelu64_backward, their Float32 forms and klstm_cell64_backward against the
+    oracle: every BFloat16 pattern as x, structured and random Float32 patterns, the fitted table and a
+    random valid one, ragged sizes, in place."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(81))
+    base = wl.all_bf16_patterns()
+    x = np.concatenate([base, base, wl.mlp_preactivations(100003, seed=82)])
+    dy = np.concatenate([rng.permutation(base), wl.f32_to_bf16_bits(rng.standard_normal(base.size + 100003, dtype=np.float32))])
+    rows = _random_valid_table(np.random.Generator(np.random.PCG64(83)), 64)
+    klut, olut = binding.KtanhLut64.from_tuples(rows), oracle.OracleLut64.from_tuples(rows)
+    dyd, xd = _to_dev(torch, dy), _to_dev(torch, x)
+    for name in ("kswish64_backward", "kgelu64_backward"):
+        with np.errstate(all="ignore"):
+            want, want_custom = getattr(oracle, name)(dy, x), getattr(oracle, name)(dy, x, olut)
+        _assert_bf16_equal(_to_host(getattr(binding, name)(dyd, xd), np.uint16), want, False, name)
+        _assert_bf16_equal(_to_host(getattr(binding, name)(dyd, xd, lut=klut), np.uint16), want_custom, False, name + " custom table")
+        for n_small in (1, 7, 8, 9, 511, 512, 513, 8192 + 13):
+            got = getattr(binding, name)(dyd[3:3 + n_small], xd[3:3 + n_small])
+            _assert_bf16_equal(_to_host(got, np.uint16), want[3:3 + n_small], False, f"{name} n={n_small}")
+        over = dyd.clone()
+        getattr(binding, name)(over, xd, dx=over)
+        _assert_bf16_equal(_to_host(over, np.uint16), want, False, name + " over dy")
+    vf = _f32_cases().view(np.float32)
+    dyf = rng.standard_normal(vf.size, dtype=np.float32)
+    vd, dyfd = torch.from_numpy(vf).to("cuda:0"), torch.from_numpy(dyf).to("cuda:0")
+    for name in ("kswish64_f32_backward", "kgelu64_f32_backward"):
+        with np.errstate(all="ignore"):
+            want, want_custom = getattr(oracle, name)(dyf, vf), getattr(oracle, name)(dyf, vf, olut)
+        _assert_f32_equal(getattr(binding, name)(dyfd, vd).cpu().numpy(), want, name)
+        _assert_f32_equal(getattr(binding, name)(dyfd, vd, lut=klut).cpu().numpy(), want_custom, name + " custom table")
+        for n_small in (1, 3, 4, 5, 255, 257, 4096 * 3 + 3):
+            got = getattr(binding, name)(dyfd[1:1 + n_small], vd[1:1 + n_small])
+            _assert_f32_equal(got.cpu().numpy(), want[1:1 + n_small], f"{name} n={n_small}")
+    for B, H in ((5, 24), (256, 2048)):
+        g3, c0 = wl.lstm_cell_inputs(1, B, H)
+        gates = g3[0]
+        edge = wl.edge_bf16_patterns()
+        gates.reshape(-1)[: edge.size] = edge
+        dh = wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32))
+        dcn = rng.standard_normal((B, H), dtype=np.float32)
+        for kl, ol in ((None, None), (klut, olut)):
+            with np.errstate(all="ignore"):
+                dg_ref, dc_ref = oracle.klstm_cell64_backward(gates, c0, dh, dcn, ol)
+            dg, dc = binding.klstm_cell64_backward(_to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0"),
+                                                   _to_dev(torch, dh), torch.from_numpy(dcn).to("cuda:0"), lut=kl)
+            _assert_bf16_equal(_to_host(dg, np.uint16).ravel(), dg_ref.ravel(), False, "dgates, 64 intervals")
+            dc = dc.cpu().numpy()
+            nanp = np.isnan(dc_ref)
+            assert np.array_equal(np.isnan(dc), nanp)
+            assert np.array_equal(dc.view(np.uint32)[~nanp], dc_ref.view(np.uint32)[~nanp])
+
+
+def test_lstm_cell_tensors_need_only_pair_alignment(gpu, oracle):
+    """gates and h 4-byte aligned, the state 8-byte aligned: views that start 4 (8) bytes into a
+    16-byte aligned buffer give the oracle's results, forward (T = 1 and T = 9) and backward."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(84))
+    B, H = 6, 40
+    for T in (1, 9):
+        gates, c0 = wl.lstm_cell_inputs(T, B, H)
+        c_ref, h_ref = oracle.klstm_cell(gates, c0)
+        gbuf = torch.zeros(gates.size + 8, dtype=torch.int16, device="cuda:0")
+        gbuf[2:2 + gates.size] = _to_dev(torch, gates).reshape(-1)
+        cbuf = torch.zeros(c0.size + 4, dtype=torch.float32, device="cuda:0")
+        cbuf[2:2 + c0.size] = torch.from_numpy(c0).to("cuda:0").reshape(-1)
+        hbuf = torch.full((T * B * H + 16,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        cout = torch.full((c0.size + 8,), 7.0, dtype=torch.float32, device="cuda:0")
+        gv, cv = gbuf[2:2 + gates.size].view(T, B, 4 * H), cbuf[2:2 + c0.size].view(B, H)
+        assert gv.data_ptr() % 16 == 4 and cv.data_ptr() % 16 == 8
+        binding.klstm_cell(gv, cv, c_out=cout[2:2 + c0.size].view(B, H), h_out=hbuf[6:6 + T * B * H].view(T, B, H))
+        res_h, res_c = _to_host(hbuf, np.uint16), cout.cpu().numpy()
+        assert np.array_equal(res_h[6:6 + T * B * H], h_ref.ravel()) and np.all(res_h[:6] == 0x5A5A) and np.all(res_h[6 + T * B * H:] == 0x5A5A)
+        assert np.array_equal(res_c[2:2 + c0.size], c_ref.ravel()) and np.all(res_c[:2] == 7.0) and np.all(res_c[2 + c0.size:] == 7.0)
+    g3, c0 = wl.lstm_cell_inputs(1, B, H)
+    dh = wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32))
+    dcn = rng.standard_normal((B, H), dtype=np.float32)
+    dg_ref, dc_ref = oracle.klstm_cell_backward(g3[0], c0, dh, dcn)
+    gbuf = torch.zeros(g3[0].size + 8, dtype=torch.int16, device="cuda:0")
+    gbuf[2:2 + g3[0].size] = _to_dev(torch, g3[0]).reshape(-1)
+    dhbuf = torch.zeros(dh.size + 8, dtype=torch.int16, device="cuda:0")
+    dhbuf[6:6 + dh.size] = _to_dev(torch, dh).reshape(-1)
+    sbuf = torch.zeros(2 * (c0.size + 4), dtype=torch.float32, device="cuda:0")
+    sbuf[2:2 + c0.size] = torch.from_numpy(c0).to("cuda:0").reshape(-1)
+    sbuf[c0.size + 6:2 * c0.size + 6] = torch.from_numpy(dcn).to("cuda:0").reshape(-1)
+    dgbuf = torch.full((g3[0].size + 8,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+    dcbuf = torch.full((c0.size + 8,), 7.0, dtype=torch.float32, device="cuda:0")
+    binding.klstm_cell_backward(gbuf[2:2 + g3[0].size].view(B, 4 * H), sbuf[2:2 + c0.size].view(B, H),
+                                dhbuf[6:6 + dh.size].view(B, H), sbuf[c0.size + 6:2 * c0.size + 6].view(B, H),
+                                dgates=dgbuf[2:2 + g3[0].size].view(B, 4 * H), dc_prev=dcbuf[2:2 + c0.size].view(B, H))
+    res_g, res_c = _to_host(dgbuf, np.uint16), dcbuf.cpu().numpy()
+    assert np.array_equal(res_g[2:2 + g3[0].size], dg_ref.ravel()) and np.all(res_g[:2] == 0x5A5A) and np.all(res_g[2 + g3[0].size:] == 0x5A5A)
+    assert np.array_equal(res_c[2:2 + c0.size], dc_ref.ravel()) and np.all(res_c[:2] == 7.0) and np.all(res_c[2 + c0.size:] == 7.0)
+
+
 def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
     """torch.autograd through ktanh, ksigmoid and two LSTM-cell steps: the gradients that reach the
     leaves must be the oracle's, chained by hand in the same order."""
@@ -816,6 +923,40 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
     _assert_bf16_equal(_to_host(g[0].grad.view(torch.int16), np.uint16).ravel(), dg1_ref.ravel(), False, "dgates step 1")
     assert np.array_equal(c0d.grad.cpu().numpy().view(np.uint32), dc0_ref.view(np.uint32))
 
+    # 64-interval tables: the fitted one through intervals=64, a caller's one through its type
+    rows = _random_valid_table(np.random.Generator(np.random.PCG64(85)), 64)
+    klut, olut = binding.KtanhLut64.from_tuples(rows), oracle.OracleLut64.from_tuples(rows)
+    for kwargs, ol in (({"intervals": 64}, None), ({"lut": klut}, olut)):
+        for fn, fwd, bwd, from_input in ((kt.ktanh, oracle.ktanh64_bf16, oracle.ktanh_backward, False),
+                                         (kt.ksigmoid, oracle.ksigmoid64, oracle.ksigmoid_backward, False),
+                                         (kt.kswish, oracle.kswish64, oracle.kswish64_backward, True),
+                                         (kt.kgelu, oracle.kgelu64, oracle.kgelu64_backward, True)):
+            xd = bf16_leaf(x)
+            yd = fn(xd, **kwargs)
+            yd.backward(_to_dev(torch, dy).view(torch.bfloat16))
+            with np.errstate(all="ignore"):
+                y_ref = fwd(x, ol)
+                g_ref = bwd(dy, x, ol) if from_input else bwd(dy, y_ref)
+            _assert_bf16_equal(_to_host(yd.detach().view(torch.int16), np.uint16), y_ref, False, fn.__name__ + " 64")
+            _assert_bf16_equal(_to_host(xd.grad.view(torch.int16), np.uint16), g_ref, False, fn.__name__ + " 64 grad")
+        xd = torch.from_numpy(xf).to("cuda:0").requires_grad_()
+        yd = kt.kgelu(xd, **kwargs)
+        yd.backward(torch.from_numpy(dyf).to("cuda:0"))
+        with np.errstate(all="ignore"):
+            _assert_f32_equal(yd.detach().cpu().numpy(), oracle.kgelu64_f32(xf, ol), "kgelu f32 64")
+            _assert_f32_equal(xd.grad.cpu().numpy(), oracle.kgelu64_f32_backward(dyf, xf, ol), "kgelu f32 64 grad")
+        g0 = bf16_leaf(gates[0])
+        c0d = torch.from_numpy(c0).to("cuda:0").requires_grad_()
+        h1, c1 = kt.klstm_cell(g0, c0d, **kwargs)
+        torch.autograd.backward([h1, c1], [_to_dev(torch, dh[0]).view(torch.bfloat16), torch.from_numpy(dc2).to("cuda:0")])
+        with np.errstate(all="ignore"):
+            dg_ref, dc_ref = oracle.klstm_cell64_backward(gates[0], c0, dh[0], dc2, ol)
+        _assert_bf16_equal(_to_host(g0.grad.view(torch.int16), np.uint16).ravel(), dg_ref.ravel(), False, "dgates 64")
+        cn = np.isnan(dc_ref)
+        assert np.array_equal(c0d.grad.cpu().numpy().view(np.uint32)[~cn], dc_ref.view(np.uint32)[~cn])
+    with pytest.raises(TypeError):
+        kt.ktanh(bf16_leaf(x), lut=binding.ktanh_default_lut(), intervals=64)
+
 
 # ------------------------------------------------------------------ random sizes and alignments
 def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, oracle):
@@ -837,7 +978,6 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
     with np.errstate(all="ignore"):
         yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
         cases = {
-            "ktanh_stream_copy": ("bf16", xb),
             "ktanh_bf16": ("bf16", yb), "ksigmoid": ("bf16", sb), "kswish": ("bf16", oracle.kswish(xb)),
             "kgelu": ("bf16", oracle.kgelu(xb)), "ktanh64_bf16": ("bf16", oracle.ktanh64_bf16(xb)),
             "ksigmoid64": ("bf16", oracle.ksigmoid64(xb)), "kswish64": ("bf16", oracle.kswish64(xb)),
@@ -852,6 +992,10 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             "ksigmoid_backward": ("grad", oracle.ksigmoid_backward(db, sb)),
             "kswish_backward": ("grad", oracle.kswish_backward(db, xb)),
             "kgelu_backward": ("grad", oracle.kgelu_backward(db, xb)),
+            "kswish64_backward": ("grad", oracle.kswish64_backward(db, xb)),
+            "kgelu64_backward": ("grad", oracle.kgelu64_backward(db, xb)),
+            "kswish64_f32_backward": ("grad32", oracle.kswish64_f32_backward(df, xf)),
+            "kgelu64_f32_backward": ("grad32", oracle.kgelu64_f32_backward(df, xf)),
             "kswish_f32_backward": ("grad32", oracle.kswish_f32_backward(df, xf)),
             "kgelu_f32_backward": ("grad32", oracle.kgelu_f32_backward(df, xf)),
             "ktanh_f32_backward": ("grad32", oracle.ktanh_f32_backward(df, xf)),
