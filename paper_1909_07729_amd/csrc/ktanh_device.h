@@ -10,6 +10,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include "ktanh_order.h"
 #include "ktanh_pack.h"
 
 namespace ktanh_device {
@@ -262,8 +263,9 @@ __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
         ksigmoid_f32_pair<true, WIDE>(w, tab, s_lo, s_hi);
         return narrow_pair(s_lo, s_hi);
     } else if constexpr (OP == OP_SWISH) {
+        // No NaN rule inside: the product with x makes a NaN input a NaN output whatever K returns.
         float s_lo, s_hi;
-        ksigmoid_f32_pair<true, WIDE>(w, tab, s_lo, s_hi);
+        ksigmoid_f32_pair<false, WIDE>(w, tab, s_lo, s_hi);
         return narrow_pair(widen_lo(w) * s_lo, widen_hi(w) * s_hi);
     } else {
         // GELU, tanh form: (x/2) * (1 + K(c * (x + a * x^3))).  (x/2) * (1 + t) and
@@ -273,7 +275,9 @@ __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
         const float x_lo = widen_lo(w), x_hi = widen_hi(w);
         const float u_lo = c * (x_lo + a * ((x_lo * x_lo) * x_lo));
         const float u_hi = c * (x_hi + a * ((x_hi * x_hi) * x_hi));
-        const uint32_t t2 = ktanh_pair<true, WIDE>(narrow_pair(u_lo, u_hi), tab);
+        // The argument is a NaN only where x is one (x + a x^3 cannot cancel: both terms carry the
+        // sign of x), and there the last product is a NaN whatever K returns: no NaN rule inside.
+        const uint32_t t2 = ktanh_pair<false, WIDE>(narrow_pair(u_lo, u_hi), tab);
         const float y_lo = x_lo * __builtin_fmaf(0.5f, widen_lo(t2), 0.5f);
         const float y_hi = x_hi * __builtin_fmaf(0.5f, widen_hi(t2), 0.5f);
         return narrow_pair(y_lo, y_hi);

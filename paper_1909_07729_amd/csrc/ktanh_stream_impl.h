@@ -43,6 +43,7 @@ template <bool F32, int OP, bool WIDE, bool IN_UNALIGNED>
 __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *vin, uint4 *vout,  // may be equal
                                                         unsigned long long nvec, unsigned skew,
                                                         unsigned n_edge /* head + tail, < 64 */,
+                                                        unsigned whole, unsigned lg_seg,  // TileOrder
                                                         EdgeArgs edge, KtLutPack pack)
 {
     const LaneTable tab(pack);
@@ -53,7 +54,8 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *vin, uint4 
     // every operation (5 % over 256-thread blocks on a 105 MB tensor, two vectors per lane another
     // 3-5 % slower): with 32 independent wavefronts per compute unit even GELU's arithmetic hides
     // under the stream.
-    const unsigned long long slot = (unsigned long long)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned long long slot =
+        (unsigned long long)tile_of_block(blockIdx.x, whole, lg_seg) * kBlock + threadIdx.x;
     const unsigned long long at = slot - skew;
     const bool live_vec = slot >= skew && at < nvec;
     uint4 v = uint4{0u, 0u, 0u, 0u};
@@ -128,11 +130,14 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
     size_t tiles = (nvec + skew + kBlock - 1) / kBlock;
     if (tiles == 0) tiles = 1;  // edges only
     if (tiles > kMaxTiles) return KT_ERR_SHAPE;
+    const TileOrder order = tile_order_for(tiles);
     if ((ain & 15) == (aout & 15))
         return launch_checked(stream_kernel<F32, OP, WIDE, false>, (unsigned)tiles, kBlock, stream,
-                              vin, vout, (unsigned long long)nvec, skew, n_edge, edge, pack);
+                              vin, vout, (unsigned long long)nvec, skew, n_edge, order.whole,
+                              order.lg_seg, edge, pack);
     return launch_checked(stream_kernel<F32, OP, WIDE, true>, (unsigned)tiles, kBlock, stream, vin,
-                          vout, (unsigned long long)nvec, skew, n_edge, edge, pack);
+                          vout, (unsigned long long)nvec, skew, n_edge, order.whole, order.lg_seg, edge,
+                          pack);
 }
 
 }  // namespace ktanh_device

@@ -3,6 +3,9 @@
 #include <cstdio>
 #include <cstring>
 
+#include <vector>
+
+#include "ktanh_order.h"
 #include "ktanh_pack.h"
 
 int main()
@@ -22,6 +25,20 @@ int main()
     if (ktanh_lut_validate(&fitted) != KT_OK || kt_pack_lut_bf16(&fitted, &pack) != KT_OK) return 7;
     fitted.b[5] = -128;
     if (ktanh_lut_validate(&fitted) != KT_ERR_LUT) return 8;
+    // the tile order is a bijection on [0, tiles) for sizes below, at and between whole segments
+    for (unsigned long long tiles : {1ull, 7ull, 51200ull, (1ull << 18) - 1, 1ull << 18, (1ull << 18) + 5,
+                                     307200ull, (1ull << 19) - 8, 1ull << 19, (1ull << 19) + 12345, 3ull << 18,
+                                     1ull << 20, (1ull << 20) + (1ull << 18) + 3}) {
+        const ktanh_device::TileOrder order = ktanh_device::tile_order_for(tiles);
+        if (order.whole > tiles || (tiles >= (1ull << 18)) != (order.whole != 0)) return 9;
+        std::vector<unsigned char> seen(tiles, 0);
+        for (unsigned b = 0; b < tiles; ++b) {
+            const unsigned t = ktanh_device::tile_of_block(b, order.whole, order.lg_seg);
+            if (t >= tiles || seen[t]) return 10;
+            seen[t] = 1;
+        }
+        if (ktanh_device::tile_of_block(0, order.whole, order.lg_seg) != 0) return 11;  // block 0 keeps the short first tile
+    }
     std::puts("host sources clean");
     return 0;
 }
