@@ -12,7 +12,8 @@ namespace {
 // arithmetic with memory rather than wide accesses; a wavefront's loads still cover 256 contiguous
 // bytes each.  The steps of one lane are sequential, so the gate words of the next kStages steps are
 // already on their way while a step is computed (a ring of register stages): without that the loop
-// would pay one full memory latency per step.
+// would pay one full memory latency per step.  The gate non-linearities of a step are formed one step
+// early, under the wait for the previous step's K(c').
 constexpr int kStages = 4;
 constexpr int kCellBlock = 256;  // four wavefronts per block measured best for the short per-step launch
 
@@ -53,50 +54,100 @@ __device__ __forceinline__ uint32_t not_finite(float x)
     return (__float_as_uint(x) & 0x7F800000u) == 0x7F800000u ? 1u : 0u;
 }
 
-// One time step for the two cells of a lane: updates their state, returns the two hidden outputs.
-// NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
-// is NaN, the incoming state is finite and the table keeps |K| <= 1 (the state then stays finite:
-// |c'| <= |c| + 1).
-template <bool NANS, bool WIDE>
-__device__ __forceinline__ uint32_t lstm_step(const GateWords &q, float &c_lo, float &c_hi,
-                                              const LaneTable &tab)
-{
-    // One gate after the other: putting all eight table reads of the four gates in flight first
-    // measured 10 % slower (the four wavefronts of a SIMD then stall and resume in step).
+// The gate non-linearities of one time step for the two cells of a lane.  They depend on the gate
+// words alone, not on the state, so they can be formed one step ahead.
+struct Acts {
     float i_lo, i_hi, f_lo, f_hi, o_lo, o_hi;
-    ksigmoid_f32_pair<NANS, WIDE>(q.i, tab, i_lo, i_hi);
-    ksigmoid_f32_pair<NANS, WIDE>(q.f, tab, f_lo, f_hi);
-    ksigmoid_f32_pair<NANS, WIDE>(q.o, tab, o_lo, o_hi);
-    const uint32_t g2 = ktanh_pair<NANS, WIDE>(q.g, tab);
-    // c' = (f * c) + (i * g): two products and one sum, each rounded on its own
-    const float keep_lo = f_lo * c_lo, keep_hi = f_hi * c_hi;
-    const float add_lo = i_lo * widen_lo(g2), add_hi = i_hi * widen_hi(g2);
-    c_lo = keep_lo + add_lo;
-    c_hi = keep_hi + add_hi;
-    const uint32_t tc2 = ktanh_pair<NANS, WIDE>(narrow_pair(c_lo, c_hi), tab);
-    return narrow_pair(o_lo * widen_lo(tc2), o_hi * widen_hi(tc2));
+    uint32_t g2;  // K(g) as a BFloat16 pair
+};
+
+// NANS = false is the same arithmetic without the NaN rules of K-TanH; it is exact whenever no gate
+// word holds a NaN.
+template <bool NANS, bool WIDE>
+__device__ __forceinline__ Acts activations(const GateWords &q, const LaneTable &tab)
+{
+    Acts a;
+    ksigmoid_f32_pair<NANS, WIDE>(q.i, tab, a.i_lo, a.i_hi);
+    ksigmoid_f32_pair<NANS, WIDE>(q.f, tab, a.f_lo, a.f_hi);
+    ksigmoid_f32_pair<NANS, WIDE>(q.o, tab, a.o_lo, a.o_hi);
+    a.g2 = ktanh_pair<NANS, WIDE>(q.g, tab);
+    return a;
 }
 
-// NaNs are rare: one test per step for the whole wavefront picks the full rules only when some
-// lane needs them (a wavefront-uniform branch, so that the cross-lane table reads still run with
-// every lane enabled).  always_checked: the caller's table lets |K| exceed 1, so the state may
-// overflow on the way.
-// `suspect` is a per-lane flag word (non-zero = this lane's state may not be finite), kept as a
-// number so that it joins the gate test with one OR.
+// c' = (f * c) + (i * g): two products and one sum, each rounded on its own.
+__device__ __forceinline__ void advance_state(const Acts &a, float2 &c)
+{
+    const float keep_lo = a.f_lo * c.x, keep_hi = a.f_hi * c.y;
+    const float add_lo = a.i_lo * widen_lo(a.g2), add_hi = a.i_hi * widen_hi(a.g2);
+    c.x = keep_lo + add_lo;
+    c.y = keep_hi + add_hi;
+}
+
+// The state update and the hidden outputs of one step from its activations, with the full NaN rules
+// (exact for any input).
 template <bool WIDE>
-__device__ __forceinline__ uint32_t guarded_step(const GateWords &q, float2 &c, uint32_t &suspect,
-                                                 uint32_t always_checked, const LaneTable &tab)
+__device__ __forceinline__ uint32_t finish_step_checked(const Acts &a, float2 &c, const LaneTable &tab)
+{
+    advance_state(a, c);
+    const uint32_t tc2 = ktanh_pair<true, WIDE>(narrow_pair(c.x, c.y), tab);
+    return narrow_pair(a.o_lo * widen_lo(tc2), a.o_hi * widen_hi(tc2));
+}
+
+// True for the whole wavefront when some lane holds a NaN in one of its four gate words.
+__device__ __forceinline__ bool gates_hold_nan(const GateWords &q)
 {
     const uint32_t worst = max_pair(max_pair(q.i & kMag2, q.f & kMag2),
                                     max_pair(q.g & kMag2, q.o & kMag2));
+    return __builtin_amdgcn_ballot_w64(nan_bits_pair(worst) != 0u) != 0;
+}
+
+// One time step, and the activations of the next one.  `a` holds the activations of this step and
+// is replaced by those of the step whose gate words are `next`; `a_checked` says (for the whole
+// wavefront) whether `a` was formed under the NaN rules, i.e. may hold a NaN.
+//
+// The steps of a lane form one dependent chain (state -> K(state) -> output), and each K costs a
+// round trip through the cross-lane unit.  With only four wavefronts per SIMD that latency is not
+// hidden by other wavefronts, so it is hidden inside the wavefront: the table reads for K(c') are
+// put in flight, the next step's activations (four independent K evaluations) are formed while they
+// travel, and only then is K(c') finished.
+//
+// NaNs are rare: the fast path drops the NaN rules and runs only when no lane of the wavefront needs
+// them (wavefront-uniform branches, so that the cross-lane table reads still run with every lane
+// enabled).  `suspect` is a per-lane flag word (non-zero = this lane's state may not be finite);
+// always_checked: the caller's table lets |K| exceed 1, so the state may overflow on the way.
+template <bool WIDE>
+__device__ __forceinline__ uint32_t step_and_look_ahead(Acts &a, bool &a_checked, const GateWords &next,
+                                                        float2 &c, uint32_t &suspect,
+                                                        uint32_t always_checked, const LaneTable &tab)
+{
+    const bool next_checked = gates_hold_nan(next);
+    const bool now_checked = a_checked || __builtin_amdgcn_ballot_w64(suspect != 0u) != 0;
     uint32_t h;
-    if (__builtin_amdgcn_ballot_w64((nan_bits_pair(worst) | suspect) != 0u) != 0) {
-        h = lstm_step<true, WIDE>(q, c.x, c.y, tab);
-        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
+    if (!now_checked && !next_checked) {
+        // exact here: no gate is a NaN, the incoming state is finite and |K| <= 1, so the state
+        // stays finite (|c'| <= |c| + 1)
+        advance_state(a, c);
+        const uint32_t cb = narrow_pair(c.x, c.y);
+        const uint32_t mag2 = cb & kMag2;
+        const SlotPair sp = fetch_slots<WIDE>(mag2, tab);
+        const Acts ahead = activations<false, WIDE>(next, tab);
+        const uint32_t tc2 = bitsel(kMag2, finish_mag_pair<WIDE>(mag2, sp), cb);
+        h = narrow_pair(a.o_lo * widen_lo(tc2), a.o_hi * widen_hi(tc2));
+        a = ahead;
     } else {
-        h = lstm_step<false, WIDE>(q, c.x, c.y, tab);
+        h = finish_step_checked<WIDE>(a, c, tab);
+        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
+        a = activations<true, WIDE>(next, tab);
     }
+    a_checked = next_checked;
     return h;
+}
+
+// The last step of a call: no next gate words to look at.
+template <bool WIDE>
+__device__ __forceinline__ uint32_t last_step(const Acts &a, float2 &c, const LaneTable &tab)
+{
+    return finish_step_checked<WIDE>(a, c, tab);
 }
 
 template <bool WIDE>
@@ -128,41 +179,43 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
     const uint32_t *ahead = gates;  // the next step to fetch
     uint32_t *h_row = h_out;        // the next step to store
     unsigned t = 0;
-    uint32_t suspect;
 
-    if (T >= 2u * kStages) {
+    const bool ring = T >= 2u * kStages;
 #pragma unroll
-        for (int s = 0; s < kStages; ++s, ahead += row_step) stage[s] = load_gates(ahead, at);
-        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
-        // Steady state: each stage is refilled right after the step that consumed it, in place
-        // (the refill follows the step's last use of the old words, so that no register copies --
-        // which would have to wait for every load in flight -- are needed at the end of the body).
+    for (int s = 0; s < kStages; ++s) {
+        stage[s] = GateWords{0u, 0u, 0u, 0u};
+        if (ring || s < (int)T) {  // uniform over the grid
+            stage[s] = load_gates(ahead, at);
+            ahead += row_step;
+        }
+    }
+    uint32_t suspect = always_checked | not_finite(c.x) | not_finite(c.y);
+    // the activations of step 0, under the full rules (once per call)
+    Acts a = activations<true, WIDE>(stage[0], tab);
+    bool a_checked = true;
+
+    if (ring) {
+        // Steady state: stage s holds the gate words of the current step, stage s + 1 those of the
+        // next; each stage is refilled right after the step that consumed it, in place (the refill
+        // follows the step's last use of the old words, so that no register copies -- which would
+        // have to wait for every load in flight -- are needed at the end of the body).
         for (; t + 2u * kStages <= T; t += kStages) {
 #pragma unroll
             for (int s = 0; s < kStages; ++s) {
-                const uint32_t h = guarded_step<WIDE>(stage[s], c, suspect, always_checked, tab);
+                const uint32_t h = step_and_look_ahead<WIDE>(a, a_checked, stage[(s + 1) % kStages], c,
+                                                             suspect, always_checked, tab);
                 if (live) store_stream(h_row, h_at, h);
                 h_row += n_pairs;
                 stage[s] = load_gates(ahead, at);
                 ahead += row_step;
             }
         }
-    } else {
-#pragma unroll
-        for (int s = 0; s < kStages; ++s) {
-            stage[s] = GateWords{0u, 0u, 0u, 0u};
-            if (s < (int)T) {  // uniform over the grid
-                stage[s] = load_gates(ahead, at);
-                ahead += row_step;
-            }
-        }
-        suspect = always_checked | not_finite(c.x) | not_finite(c.y);
     }
 
     // The last steps (fewer than 2 * kStages): stage[0] is the current one, the ring moves up.
     const uint32_t *const gates_end = gates + (unsigned long long)T * row_step;
-    for (; t < T; ++t) {
-        const uint32_t h = guarded_step<WIDE>(stage[0], c, suspect, always_checked, tab);
+    for (; t + 1 < T; ++t) {
+        const uint32_t h = step_and_look_ahead<WIDE>(a, a_checked, stage[1], c, suspect, always_checked, tab);
         if (live) store_stream(h_row, h_at, h);
         h_row += n_pairs;
 #pragma unroll
@@ -173,6 +226,8 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
             ahead += row_step;
         }
     }
+    const uint32_t h = last_step<WIDE>(a, c, tab);
+    if (live) store_stream(h_row, h_at, h);
     if (live) c_out[p] = c;
 }
 
