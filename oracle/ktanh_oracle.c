@@ -52,6 +52,13 @@
  *                          through a 64-interval table that repeats Table 1,
  *                          which must give the 32-interval gradients, and by
  *                          hand-worked values)
+ *   oracle_kpade32, oracle_kpade78
+ *                          the rational Pade[3/2] and Pade[7/8] approximants
+ *                          of Section 2 that Table 2 compares K-TanH with
+ *                          (coefficients pinned by an exact re-derivation from
+ *                          the definition; the two error figures Table 2
+ *                          prints for each do not follow from the text alone
+ *                          and are held as loose bounds only)
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
@@ -798,6 +805,87 @@ void oracle_klstm_cell64_backward(const uint16_t *gates, const float *c_prev, co
 {
     klstm_backward_fields(gates, c_prev, dh, dc_next, dgates, dc_prev, B, H, 4, lut->E, lut->r,
                           lut->b);
+}
+
+/* ------------------------------------------------------------------ */
+/* The rational Pade approximants the paper compares K-TanH with (Section 2,
+ * "Pade rational Polynomial"; rows "Rational Pade 3/2" and "7/8" of Table 2):
+ *   Pade[p/q](x) = (a_0 + a_1 x + ... + a_p x^p) / (b_0 + b_1 x + ... + b_q x^q)
+ * whose value and first p+q derivatives at zero are those of TanH.  Solving that
+ * system for TanH and scaling to the smallest integers gives
+ *   [3/2]:  x (15 + x^2) / (15 + 6 x^2)
+ *   [7/8]:  x (2027025 + 270270 x^2 + 6930 x^4 + 36 x^6)
+ *           / (2027025 + 945945 x^2 + 51975 x^4 + 630 x^6 + x^8)
+ * (the test-suite re-derives both from the Taylor series of TanH in exact
+ * rational arithmetic).  The paper gives no evaluation order, range handling or
+ * precision; taken here: BFloat16 in and out, Float32 arithmetic, one rounding
+ * per written operation, Horner's scheme in x^2 on the magnitude of x, the sign
+ * put back at the end.  [3/2] grows without bound, so it is evaluated on
+ * min(|x|, 4) and capped at 1; [7/8] peaks at |x| = 5.70 (0.99995) and decays
+ * beyond, so it is evaluated on min(|x|, 5.5).  A NaN is returned quieted. */
+void oracle_pade_coefficients(int which, double *num, double *den)
+{
+    /* coefficients of x^0, x^1, ...; which = 32 or 78 */
+    if (which == 32) {
+        const double a[4] = {0, 15, 0, 1}, b[3] = {15, 0, 6};
+        memcpy(num, a, sizeof a);
+        memcpy(den, b, sizeof b);
+    } else {
+        const double a[8] = {0, 2027025, 0, 270270, 0, 6930, 0, 36};
+        const double b[9] = {2027025, 0, 945945, 0, 51975, 0, 630, 0, 1};
+        memcpy(num, a, sizeof a);
+        memcpy(den, b, sizeof b);
+    }
+}
+
+static uint16_t with_sign_of(uint16_t x, float magnitude)
+{
+    return (uint16_t)(narrow_rne(magnitude) | (x & 0x8000u));
+}
+
+void oracle_kpade32(const uint16_t *in, uint16_t *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        uint16_t x = in[i];
+        if ((x & 0x7FFFu) > 0x7F80u) { out[i] = (uint16_t)(x | 0x0040u); continue; }
+        float a = widen((uint16_t)(x & 0x7FFFu));
+        if (a > 4.0f) a = 4.0f;
+        float x2 = a * a;
+        float top = 15.0f + x2;
+        float num = a * top;
+        float six = 6.0f * x2;
+        float den = 15.0f + six;
+        float y = num / den;
+        if (y > 1.0f) y = 1.0f;
+        out[i] = with_sign_of(x, y);
+    }
+}
+
+void oracle_kpade78(const uint16_t *in, uint16_t *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i) {
+        uint16_t x = in[i];
+        if ((x & 0x7FFFu) > 0x7F80u) { out[i] = (uint16_t)(x | 0x0040u); continue; }
+        float a = widen((uint16_t)(x & 0x7FFFu));
+        if (a > 5.5f) a = 5.5f;
+        float x2 = a * a;
+        float p = 36.0f * x2;
+        p = p + 6930.0f;
+        p = p * x2;
+        p = p + 270270.0f;
+        p = p * x2;
+        p = p + 2027025.0f;
+        float num = a * p;
+        float q = x2 + 630.0f;
+        q = q * x2;
+        q = q + 51975.0f;
+        q = q * x2;
+        q = q + 945945.0f;
+        q = q * x2;
+        q = q + 2027025.0f;
+        float y = num / q;
+        out[i] = with_sign_of(x, y);
+    }
 }
 
 /* ------------------------------------------------------------------ */

@@ -121,6 +121,11 @@ def _load():
         lib.oracle_klstm_cell64_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, sz,
                                                      ctypes.POINTER(OracleLut64)]
         lib.oracle_klstm_cell64_backward.restype = None
+        for name in ("oracle_kpade32", "oracle_kpade78"):
+            getattr(lib, name).argtypes = [vp, vp, sz]
+            getattr(lib, name).restype = None
+        lib.oracle_pade_coefficients.argtypes = [ctypes.c_int, vp, vp]
+        lib.oracle_pade_coefficients.restype = None
         lp64 = ctypes.POINTER(OracleLut64)
         lib.oracle_fit_lut64.argtypes = [lp64]
         for name in ("oracle_ktanh64_bf16", "oracle_ktanh64_f32", "oracle_ksigmoid64", "oracle_kswish64",
@@ -312,6 +317,31 @@ def klstm_cell(gates_bits, c_in, lut=None):
     _load().oracle_klstm_cell(gates.ctypes.data, c_in.ctypes.data, c_out.ctypes.data,
                               h_out.ctypes.data, T, B, H, ctypes.byref(lut))
     return c_out, h_out
+
+
+def _pade(name, x_bits):
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    out = np.empty_like(x)
+    getattr(_load(), name)(x.ctypes.data, out.ctypes.data, x.size)
+    return out
+
+
+def kpade32(x_bits):
+    """The Pade[3/2] approximant of TanH, BFloat16 bits in and out."""
+    return _pade("oracle_kpade32", x_bits)
+
+
+def kpade78(x_bits):
+    """The Pade[7/8] approximant of TanH, BFloat16 bits in and out."""
+    return _pade("oracle_kpade78", x_bits)
+
+
+def pade_coefficients(which):
+    """(numerator, denominator) coefficient lists of x^0, x^1, ... for which = 32 or 78."""
+    p, q = (3, 2) if which == 32 else (7, 8)
+    num, den = np.zeros(p + 1), np.zeros(q + 1)
+    _load().oracle_pade_coefficients(which, num.ctypes.data, den.ctypes.data)
+    return num.tolist(), den.tolist()
 
 
 def _backward(name, dy_bits, fwd_bits):

@@ -837,6 +837,69 @@ def test_gradients_on_64_interval_tables(oracle):
     assert np.all(np.abs(_bf16_val(got[ok]) - want[ok]) <= 2.0 ** -8 * np.abs(want[ok]) + 1e-6 * np.abs(dv[ok]) * (1 + np.abs(xv[ok]) ** 3))
 
 
+def test_pade_approximants(oracle):
+    """Pade[3/2] and Pade[7/8] (Section 2): the coefficients re-derived here from the definition --
+    value and first p+q derivatives at zero equal to TanH's -- in exact rational arithmetic; values by
+    hand; float64 re-evaluation of the quotient; the distance to TanH; odd symmetry, saturation, NaN."""
+    from fractions import Fraction as F
+    # Taylor coefficients of TanH at 0 from tanh' = 1 - tanh^2
+    N = 16
+    c = [F(0)] * (N + 1)
+    c[1] = F(1)
+    for n in range(1, N):
+        square_n = sum(c[k] * c[n - k] for k in range(n + 1))        # coefficient of x^n in tanh^2
+        c[n + 1] = (F(1 if n == 0 else 0) - square_n) / (n + 1)
+    assert c[3] == F(-1, 3) and c[5] == F(2, 15) and c[7] == F(-17, 315)
+
+    def pade(p, q):
+        # b_0 = 1; sum_{j=0..q} b_j c_{k-j} = 0 for k = p+1 .. p+q  (q equations, q unknowns b_1..b_q)
+        rows = [[c[k - j] if k - j >= 0 else F(0) for j in range(1, q + 1)] + [-c[k]] for k in range(p + 1, p + q + 1)]
+        for col in range(q):                                           # Gauss-Jordan on fractions
+            piv = next(r for r in range(col, q) if rows[r][col] != 0)
+            rows[col], rows[piv] = rows[piv], rows[col]
+            rows[col] = [v / rows[col][col] for v in rows[col]]
+            for r in range(q):
+                if r != col and rows[r][col] != 0:
+                    rows[r] = [a - rows[r][col] * b for a, b in zip(rows[r], rows[col])]
+        b = [F(1)] + [rows[j][q] for j in range(q)]
+        a = [sum(b[j] * c[k - j] for j in range(min(k, q) + 1)) for k in range(p + 1)]
+        return a, b
+
+    for which, (p, q) in ((32, (3, 2)), (78, (7, 8))):
+        a, b = pade(p, q)
+        num, den = oracle.pade_coefficients(which)
+        scale = F(int(den[0]))                                        # the oracle's integer scaling: b_0 -> den[0]
+        assert [x * scale for x in a] == [F(int(v)) for v in num], which
+        assert [x * scale for x in b] == [F(int(v)) for v in den], which
+
+    one = lambda fn, bits: int(fn(np.array([bits], np.uint16))[0])
+    # [3/2]: 1 -> 16/21 = 0.76190 -> 0x3F43;  0.5 -> 0.5*15.25/16.5 = 0.462121 -> 0x3EED;  2 -> 38/39 = 0.974359 -> 0x3F79
+    assert one(oracle.kpade32, 0x3F80) == 0x3F43 and one(oracle.kpade32, 0x3F00) == 0x3EED and one(oracle.kpade32, 0x4000) == 0x3F79
+    # 3 -> 72/69 > 1: capped;  -2 -> sign restored;  [7/8]: 1 -> 2304261/3025576 = 0.7615942 -> 0x3F43
+    assert one(oracle.kpade32, 0x4040) == 0x3F80 and one(oracle.kpade32, 0xC000) == 0xBF79
+    assert one(oracle.kpade78, 0x3F80) == 0x3F43 and one(oracle.kpade78, 0x40B0) == 0x3F80 and one(oracle.kpade78, 0x7F80) == 0x3F80
+    for fn in (oracle.kpade32, oracle.kpade78):
+        assert one(fn, 0x7FC1) == 0x7FC1 and one(fn, 0xFF81) == 0xFFC1 and one(fn, 0x0000) == 0x0000 and one(fn, 0x8000) == 0x8000
+
+    x = _finite_bf16()
+    xv = _bf16_val(x)
+    t = np.tanh(xv)
+    for which, fn, cut, cap, bound in ((32, oracle.kpade32, 4.0, 1.0, 1.905e-2 + 2.0 ** -9), (78, oracle.kpade78, 5.5, np.inf, 2.0 ** -9 + 1e-4)):
+        num, den = oracle.pade_coefficients(which)
+        a = np.minimum(np.abs(xv), cut)
+        want = np.sign(xv) * np.minimum(np.polyval(num[::-1], a) / np.polyval(den[::-1], a), cap)
+        got = fn(x)
+        assert np.max(_ulp_distance_bf16(got, _round_f64_to_bf16(want))) <= 1, which
+        assert np.array_equal(fn(x ^ 0x8000), got ^ 0x8000), which
+        err = np.abs(_bf16_val(got) - t)
+        assert err.max() <= bound, (which, err.max())
+    # Table 2 prints 2.35e-2 and 2.59 % for [3/2]: an upper bound for this reading (1.90e-2 and 1.94 % before the
+    # result is rounded to BFloat16, 2.00e-2 after);
+    # for [7/8] it prints 1e-4, below what a BFloat16 result can hold (half an ulp near 1 is 2e-3)
+    e32 = np.abs(_bf16_val(oracle.kpade32(x)) - t)
+    assert 1.8e-2 < e32.max() <= 2.35e-2 and np.max(e32[t != 0] / np.abs(t[t != 0])) <= 2.59e-2
+
+
 def test_checksums_against_an_independent_implementation(oracle):
     """All 65,536 outputs of the four BFloat16 operations, as CRC32, against values recorded from
     an implementation that shares nothing with this oracle."""
