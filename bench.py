@@ -254,6 +254,9 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
            lambda i: probe.ktanh_probe_copy(xs[i % ROTATE], ys[i % ROTATE]), n2, 4, 1000, 200)
     record("ktanh64_bf16", "[50,128,4096] bf16 as in the headline, 64-interval table, 8 rotating buffer pairs",
            lambda i: binding.ktanh64_bf16(xs[i % ROTATE], out=ys[i % ROTATE]), n2, 4, 1000, 200)
+    for name in ("kpade32_bf16", "kpade78_bf16"):
+        record(name, "Table 2's rational approximant (Float32 arithmetic with a division) on the headline tensor, 8 rotating pairs",
+               lambda i, fn=getattr(binding, name): fn(xs[i % ROTATE], out=ys[i % ROTATE]), n2, 4, 1000, 200)
     record("ktanh_bf16_backward", "dy, y and dx as the headline tensor (6 B per element), 8 rotating triples",
            lambda i: binding.ktanh_bf16_backward(xs[i % ROTATE], ys[(i + 1) % ROTATE], dx=ys[i % ROTATE]),
            n2, 6, 1000, 200)
@@ -268,7 +271,7 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
         x4.append(x4[0].roll(k * 4099))
     y4 = [torch.empty_like(t) for t in x4]
     n4 = x4[0].numel()
-    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu"):
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16"):
         fn = getattr(binding, name)
         record(f"{name}_mlp", "[8192,16384] bf16 ~ N(0,1), seed 190904, 4 rotating buffer pairs",
                lambda i, fn=fn: fn(x4[i % 4], out=y4[i % 4]), n4, 4, 200, 60)
@@ -456,7 +459,7 @@ def run_probe(torch, binding, probe, wl, upload, headline):
         x4.append(x4[0].roll(k * 4099))
     y4 = [torch.empty_like(t) for t in x4]
     sink = torch.zeros(512, dtype=torch.int16, device=x4[0].device)
-    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu"):
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16"):
         for k in range(20):
             getattr(binding, name)(x4[k % 4], out=y4[k % 4])
     for k in range(20):

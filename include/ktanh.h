@@ -251,6 +251,21 @@ ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev, c
                                    size_t H, const ktanh_lut_t *lut, ktanh_stream_t stream);
 
 
+/* ---- Comparison approximants ---------------------------------------------------------------------
+ * The rational Pade approximants of Section 2 ("Pade rational Polynomial"), which Table 2 sets
+ * against K-TanH: the quotient of two polynomials whose value and first p+q derivatives at zero are
+ * TanH's, scaled to integer coefficients:
+ *   kpade32_bf16:  x (15 + x^2) / (15 + 6 x^2)                      evaluated on min(|x|, 4), capped at 1
+ *   kpade78_bf16:  x (2027025 + 270270 x^2 + 6930 x^4 + 36 x^6)
+ *                  / (2027025 + 945945 x^2 + 51975 x^4 + 630 x^6 + x^8)   evaluated on min(|x|, 5.5)
+ * (the first grows without bound, the second peaks at |x| = 5.70 and decays: hence the cut-offs, which
+ * the paper does not give).  BFloat16 in and out, n elements each, device; Float32 arithmetic, one
+ * rounding per operation, Horner's scheme in x^2 on |x|, correctly rounded division, the sign put
+ * back, the result rounded to nearest even; a NaN is returned quieted.  No table is involved.
+ * Same conventions (alignment, aliasing, sizes, errors) as ktanh_bf16. */
+ktanh_status_t kpade32_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
+ktanh_status_t kpade78_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
+
 /* The gradients that read a table, with a 64-interval table (Section 2.4, last paragraph) inside:
  * the same formulas and operation order with K = ktanh64_bf16 (ktanh64_f32 on Float32 tensors).
  * `lut` == NULL selects the fitted 64-interval table.  (ktanh_bf16_backward, ksigmoid_backward and

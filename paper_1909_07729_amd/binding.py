@@ -35,6 +35,7 @@ SIGNATURES = {
     "kswish64_backward": "pppnLs", "kgelu64_backward": "pppnLs",
     "kswish64_f32_backward": "pppnLs", "kgelu64_f32_backward": "pppnLs",
     "klstm_cell_backward": "ppppppnnls", "klstm_cell64_backward": "ppppppnnLs",
+    "kpade32_bf16": "ppns", "kpade78_bf16": "ppns",
 }
 EXPORTS = tuple(SIGNATURES)
 
@@ -194,6 +195,29 @@ def _elementwise(name, x, out, lut, stream, dtypes):
 def ktanh_bf16(x, out=None, lut=None, stream=None):
     """K-TanH on a BFloat16 tensor (or its int16/uint16 bit view); ``out`` may be ``x``."""
     return _elementwise("ktanh_bf16", x, out, lut, stream, _BF16_VIEWS)
+
+
+def _pade(name, x, out, stream):
+    _check(x, _BF16_VIEWS, "in")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(out, _BF16_VIEWS, "out")
+    if out.numel() != x.numel():
+        raise ValueError("in and out differ in size")
+    st = getattr(load_library(), name)(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, name)
+    return out
+
+
+def kpade32_bf16(x, out=None, stream=None):
+    """The Pade[3/2] approximant of TanH (a comparison row of the paper's Table 2) on BFloat16."""
+    return _pade("kpade32_bf16", x, out, stream)
+
+
+def kpade78_bf16(x, out=None, stream=None):
+    """The Pade[7/8] approximant of TanH (a comparison row of the paper's Table 2) on BFloat16."""
+    return _pade("kpade78_bf16", x, out, stream)
 
 
 def ktanh_f32(x, out=None, lut=None, stream=None):

@@ -250,7 +250,46 @@ __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offse
 
 // OP_COPY moves the data unchanged: the same accesses with no arithmetic, the yardstick for what the
 // memory system allows in this launch shape.
-enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_COPY = 4 };
+// OP_PADE32 / OP_PADE78: the rational approximants of Section 2 that Table 2 compares K-TanH with.
+enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_COPY = 4, OP_PADE32 = 5, OP_PADE78 = 6 };
+
+// Pade[3/2] = x (15 + x^2) / (15 + 6 x^2) on min(|x|, 4), capped at 1;
+// Pade[7/8] = x (2027025 + 270270 x^2 + 6930 x^4 + 36 x^6) / (2027025 + 945945 x^2 + 51975 x^4 + 630 x^6 + x^8)
+// on min(|x|, 5.5).  Float32, one rounding per operation (Horner in x^2), correctly rounded division.
+template <int OP>
+__device__ __forceinline__ float pade_of_magnitude(float a)
+{
+    if constexpr (OP == OP_PADE32) {
+        a = a > 4.0f ? 4.0f : a;
+        const float x2 = a * a;
+        const float num = a * (15.0f + x2);
+        const float den = 15.0f + 6.0f * x2;
+        const float y = num / den;
+        return y > 1.0f ? 1.0f : y;
+    } else {
+        a = a > 5.5f ? 5.5f : a;
+        const float x2 = a * a;
+        float p = 36.0f * x2 + 6930.0f;
+        p = p * x2 + 270270.0f;
+        p = p * x2 + 2027025.0f;
+        const float num = a * p;
+        float q = x2 + 630.0f;
+        q = q * x2 + 51975.0f;
+        q = q * x2 + 945945.0f;
+        q = q * x2 + 2027025.0f;
+        return num / q;
+    }
+}
+
+// Both halves of w: magnitudes through the approximant, signs put back, NaNs returned quieted.
+template <int OP>
+__device__ __forceinline__ uint32_t pade_pair(uint32_t w)
+{
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t y2 = narrow_pair(pade_of_magnitude<OP>(widen_lo(mag2)), pade_of_magnitude<OP>(widen_hi(mag2)));
+    const uint32_t res = bitsel(kMag2, y2, w);
+    return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
+}
 
 // WIDE selects the 64-interval table layout.
 template <int OP, bool WIDE = false>
@@ -258,6 +297,8 @@ __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
 {
     if constexpr (OP == OP_COPY) {
         return w;
+    } else if constexpr (OP == OP_PADE32 || OP == OP_PADE78) {
+        return pade_pair<OP>(w);
     } else if constexpr (OP == OP_TANH) {
         return ktanh_pair<true, WIDE>(w, tab);
     } else if constexpr (OP == OP_SIGMOID) {

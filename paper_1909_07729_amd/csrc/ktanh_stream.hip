@@ -187,3 +187,13 @@ extern "C" ktanh_status_t kgelu64_f32(const float *in, float *out, size_t n,
 {
     return launch_elementwise<true, OP_GELU>(in, out, n, lut, stream);
 }
+
+extern "C" ktanh_status_t kpade32_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_PADE32>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
+}
+
+extern "C" ktanh_status_t kpade78_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_PADE78>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
+}

@@ -7,7 +7,8 @@ For each table (Table 1, the 64-interval fit, the ablation's b_min = 0 fit) ever
 input goes through the GPU kernel and the result is compared with TanH in double precision; the
 derived Sigmoid, Swish and GELU are compared with their exact forms on |x| <= 16.  Throughput is
 taken on a [50, 128, 4096] BFloat16 tensor.  (The ablation's row shows the two error figures that
-Table 2 of the paper prints for K-TanH, 1.67e-2 and 3.03 %.)  The reference values are numpy's,
+Table 2 of the paper prints for K-TanH, 1.67e-2 and 3.03 %.)  The rational Pade approximants of
+Section 2, which Table 2 compares K-TanH with, are measured the same way.  The reference values are numpy's,
 computed here; the library's arithmetic is not repeated on the CPU.
 """
 from __future__ import annotations
@@ -74,6 +75,22 @@ def error_rows() -> list[dict]:
     return rows
 
 
+def comparator_rows() -> list[dict]:
+    """The rational Pade approximants that Table 2 of the paper sets against K-TanH: the same error
+    figures and throughput, measured with this library's kernels."""
+    bits = wl.all_bf16_patterns()
+    bits = bits[(bits & 0x7FFF) < 0x7F80]
+    x = _values(bits)
+    want = np.tanh(x)
+    nz = want != 0
+    rows = []
+    for name, fn in (("Pade[3/2]", binding.kpade32_bf16), ("Pade[7/8]", binding.kpade78_bf16)):
+        err = np.abs(_values(_on_gpu(fn, bits)) - want)
+        rows.append({"approximant": name, "max_abs": float(err.max()), "at": f"0x{int(bits[int(np.argmax(err))]):04X}",
+                     "max_rel": float(np.max(err[nz] / np.abs(want[nz]))), "elements_per_s": _throughput(fn)})
+    return rows
+
+
 def derived_rows() -> list[dict]:
     """Errors of the derived activations against their exact forms on |x| <= 16, 32 and 64 intervals."""
     bits = wl.all_bf16_patterns()
@@ -108,6 +125,12 @@ def main() -> None:
     for r in error_rows():
         print(f"{r['table']:36s} {r['max_abs']:9.5f} {r['at']:>7s} {100 * r['max_rel']:7.2f}% "
               f"{r['mean_abs_region']:18.5f} {r['elements_per_s'] / 1e9:9.1f}")
+    print()
+    print("Table 2's rational approximants (Float32 arithmetic, BFloat16 in and out) against TanH (double)")
+    print(f"{'approximant':36s} {'max abs':>9s} {'at':>7s} {'max rel':>8s} {'Gelem/s':>9s}")
+    for r in comparator_rows():
+        print(f"{r['approximant']:36s} {r['max_abs']:9.5f} {r['at']:>7s} {100 * r['max_rel']:7.2f}% "
+              f"{r['elements_per_s'] / 1e9:9.1f}")
     print()
     print("Derived activations against their exact forms, |x| <= 16")
     print(f"{'operation':20s} {'max abs (32)':>13s} {'mean abs (32)':>14s} {'max abs (64)':>13s} {'mean abs (64)':>14s}")

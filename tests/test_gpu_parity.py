@@ -978,6 +978,7 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
     with np.errstate(all="ignore"):
         yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
         cases = {
+            "kpade32_bf16": ("bf16", oracle.kpade32(xb)), "kpade78_bf16": ("bf16", oracle.kpade78(xb)),
             "ktanh_bf16": ("bf16", yb), "ksigmoid": ("bf16", sb), "kswish": ("bf16", oracle.kswish(xb)),
             "kgelu": ("bf16", oracle.kgelu(xb)), "ktanh64_bf16": ("bf16", oracle.ktanh64_bf16(xb)),
             "ksigmoid64": ("bf16", oracle.ksigmoid64(xb)), "kswish64": ("bf16", oracle.kswish64(xb)),
@@ -1046,6 +1047,27 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
             assert np.all(res[:16 + o] == 0x5A5A5A5A) and np.all(res[16 + o + n:] == 0x5A5A5A5A), what
 
 
+# ------------------------------------------------------------------ Table 2's comparison approximants
+def test_pade_comparators(gpu, oracle):
+    """kpade32_bf16 and kpade78_bf16 against the oracle, bit for bit (same Float32 operations in the
+    same order, correctly rounded division on both sides): every BFloat16 pattern, a ragged sample of
+    the transformer-MLP tensor at an odd offset, in place."""
+    binding, torch = gpu
+    x = np.concatenate([wl.all_bf16_patterns(), wl.mlp_preactivations(100003, seed=86)])
+    xd = _to_dev(torch, x)
+    for name, ref in (("kpade32_bf16", oracle.kpade32), ("kpade78_bf16", oracle.kpade78)):
+        want = ref(x)
+        assert np.array_equal(_to_host(getattr(binding, name)(xd), np.uint16), want), name
+        n = 50021
+        outd = torch.full((n + 24,), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        getattr(binding, name)(xd[3:3 + n], out=outd[9:9 + n])
+        res = _to_host(outd, np.uint16)
+        assert np.array_equal(res[9:9 + n], want[3:3 + n]) and np.all(res[:9] == 0x5A5A) and np.all(res[9 + n:] == 0x5A5A), name
+        over = xd.clone()
+        getattr(binding, name)(over, out=over)
+        assert np.array_equal(_to_host(over, np.uint16), want), name + " in place"
+
+
 # ------------------------------------------------------------------ the accuracy report
 def test_accuracy_report_figures_equal_the_oracle_s(gpu, oracle):
     """paper_1909_07729_amd.report measures the three tables with the GPU kernels; the error figures
@@ -1064,6 +1086,11 @@ def test_accuracy_report_figures_equal_the_oracle_s(gpu, oracle):
         assert row["elements_per_s"] > 1e11
     assert rows[0]["max_abs"] < rows[1]["max_abs"] < rows[2]["max_abs"]
     assert rows[1]["mean_abs_region"] < rows[0]["mean_abs_region"] < rows[2]["mean_abs_region"]
+    comp = report.comparator_rows()
+    assert [r["approximant"] for r in comp] == ["Pade[3/2]", "Pade[7/8]"]
+    for row, ref in zip(comp, (oracle.kpade32, oracle.kpade78)):
+        err = np.abs(wl.bf16_bits_to_f32(ref(bits)).astype(np.float64) - np.tanh(x))
+        assert row["max_abs"] == float(err.max()) and row["elements_per_s"] > 1e11
     derived = report.derived_rows()
     assert [r["op"] for r in derived] == ["Sigmoid", "Swish", "GELU (tanh form)"]
     assert all(r["mean_abs_64"] < r["mean_abs_32"] for r in derived)
