@@ -339,25 +339,28 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
 
 
 def run_size_sweep(torch, binding, pool_in, pool_out):
-    """ktanh_bf16 on slices of 2^22 .. 2^27 elements (16.8 .. 537 MB of traffic), each size rotating
-    over distinct slices of the big buffers (at least 1 GB touched per cycle), median of three groups of 48 launches;
-    then the least-squares line  duration = fixed + bytes / rate  through the points."""
+    """ktanh_bf16 on slices of 2^24 .. 2^27 elements (67 .. 537 MB of traffic; below that a call from
+    Python takes longer to issue than the kernel to run), each size rotating over distinct slices of
+    the big buffers (at least 1 GB touched per cycle), median of three groups of 48 launches; then the
+    least-squares line  duration = fixed + bytes / rate  through the points below 256 MiB of output
+    (from there on the kernel runs two windows through the tensor, which is faster)."""
     points = []
     whole = pool_in[0].numel()
     pool_in, pool_out = [t.view(-1) for t in pool_in], [t.view(-1) for t in pool_out]
-    for lg in range(22, 28):
-        n = 1 << lg
+    for n in (1 << 24, 3 << 23, 1 << 25, 3 << 24, 1 << 26, 3 << 25, 1 << 27):
         per = whole // n
         pairs = [(pool_in[k // per][(k % per) * n:(k % per + 1) * n], pool_out[k // per][(k % per) * n:(k % per + 1) * n])
                  for k in range(min(len(pool_in) * per, max(4, (1 << 28) // n)))]
         _, _, per_launch = time_steps(torch, lambda i: binding.ktanh_bf16(pairs[i % len(pairs)][0], out=pairs[i % len(pairs)][1]),
                                       48, 16, groups=3)
         points.append((4.0 * n, statistics.median(per_launch)))
-    mx = sum(b for b, _ in points) / len(points)
-    my = sum(t for _, t in points) / len(points)
-    slope = sum((b - mx) * (t - my) for b, t in points) / sum((b - mx) ** 2 for b, _ in points)
-    return {"workload": "ktanh_bf16 on 2^22..2^27 bf16 elements, rotating slices, median of three groups of 48 launches each",
+    line = [(b, t) for b, t in points if b < 4.0 * (1 << 27)]
+    mx = sum(b for b, _ in line) / len(line)
+    my = sum(t for _, t in line) / len(line)
+    slope = sum((b - mx) * (t - my) for b, t in line) / sum((b - mx) ** 2 for b, _ in line)
+    return {"workload": "ktanh_bf16 on 2^24..2^27 bf16 elements, rotating slices, median of three groups of 48 launches each",
             "points": [{"traffic_mb": b / 1e6, "median_launch_us": t * 1e6, "gb_per_s": b / t / 1e9} for b, t in points],
+            "fit_over": "the six sizes below 256 MiB of output",
             "fit_fixed_us_per_launch": (my - slope * mx) * 1e6, "fit_asymptotic_gb_per_s": 1.0 / slope / 1e9}
 
 
@@ -501,8 +504,9 @@ def run_probe(torch, binding, probe, wl, upload, headline):
     for t in range(24):
         binding.klstm_cell(gates[t:t + 1], c0, c_out=c, h_out=h_rot[0][t:t + 1])
     dh = torch.zeros((c0.shape[0], c0.shape[1]), dtype=gates.dtype, device=gates.device)
+    dc_next = torch.ones_like(c0)
     for t in range(24):
-        binding.klstm_cell_backward(gates[t], c0, dh, c0)
+        binding.klstm_cell_backward(gates[t], c0, dh, dc_next)
     torch.cuda.synchronize()
     print("probe done")
 
