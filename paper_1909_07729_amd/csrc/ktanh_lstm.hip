@@ -212,22 +212,29 @@ __global__ __launch_bounds__(kCellBlock) void lstm_cell_kernel(const uint32_t *_
         }
     }
 
-    // The last steps (fewer than 2 * kStages): stage[0] is the current one, the ring moves up.
-    const uint32_t *const gates_end = gates + (unsigned long long)T * row_step;
-    for (; t + 1 < T; ++t) {
-        const uint32_t h = step_and_look_ahead<WIDE>(a, a_checked, stage[1], c, suspect, always_checked, tab);
-        if (live) store_stream(h_row, h_at, h);
-        h_row += n_pairs;
+    // The last steps (fewer than 2 * kStages): stage k % kStages holds step t + k.  Written out step
+    // by step with the stages named statically, like the steady loop: moving the ring up through
+    // register copies instead would make every one of these steps wait for all loads in flight,
+    // a full memory latency each.  All conditions are uniform over the grid.
 #pragma unroll
-        for (int s = 0; s + 1 < kStages; ++s) stage[s] = stage[s + 1];
-        stage[kStages - 1] = GateWords{0u, 0u, 0u, 0u};
-        if (ahead != gates_end) {  // uniform over the grid
-            stage[kStages - 1] = load_gates(ahead, at);
-            ahead += row_step;
+    for (int k = 0; k < 2 * kStages - 1; ++k) {
+        if (t + k < T) {
+            constexpr int kRing = kStages;
+            const int s = k % kRing;
+            uint32_t h;
+            if (t + k + 1 < T)
+                h = step_and_look_ahead<WIDE>(a, a_checked, stage[(s + 1) % kRing], c, suspect,
+                                              always_checked, tab);
+            else
+                h = last_step<WIDE>(a, c, tab);
+            if (live) store_stream(h_row, h_at, h);
+            h_row += n_pairs;
+            if (k < kRing && t + k + kRing < T) {
+                stage[s] = load_gates(ahead, at);
+                ahead += row_step;
+            }
         }
     }
-    const uint32_t h = last_step<WIDE>(a, c, tab);
-    if (live) store_stream(h_row, h_at, h);
     if (live) c_out[p] = c;
 }
 
