@@ -59,6 +59,13 @@
  *                          the definition; the two error figures Table 2
  *                          prints for each do not follow from the text alone
  *                          and are held as loose bounds only)
+ *   oracle_ktaylor2, oracle_ktaylor3
+ *                          Table 2's two Taylor rows under a stated reading
+ *                          (the paper defines neither partition nor expansion
+ *                          point): piecewise about the midpoints of K-TanH's
+ *                          own 32 intervals.  Parity unpinned by the paper;
+ *                          pinned by Taylor's remainder bound, the midpoints
+ *                          and the regions
  *   oracle_fit_lut64, oracle_ktanh64_bf16/f32
  *                          the 64-interval variant the last paragraph of
  *                          Section 2.4 mentions (6-bit index: 2 LSBs of the
@@ -887,6 +894,73 @@ void oracle_kpade78(const uint16_t *in, uint16_t *out, size_t n)
         out[i] = with_sign_of(x, y);
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* The rows "Taylor approx degree 2" and "degree 3" of Table 2.  The paper names
+ * the method (Section 1: Taylor expansions as one family of polynomial
+ * approximations) and prints two error figures per row, but no expansion
+ * point, partition or range handling.  Taken here, so that the row stands next
+ * to K-TanH like with like: the same partition and the same regions as
+ * Algorithm 1 -- |x| < T1 = 0.25 passes through, |x| >= 4 gives +-1, and
+ * [0.25, 4) is cut into the 32 intervals that the index t of Table 1 names
+ * (2 low exponent bits, 3 high mantissa bits) -- and on each interval the
+ * Taylor polynomial of TanH about the interval's midpoint a_t,
+ *   T_n(x) = sum_{k <= n} D^k TanH(a_t) / k! * (|x| - a_t)^k,
+ * with the derivatives obtained by differentiating D TanH = 1 - TanH^2 again
+ * and again.  A table entry is then n + 1 Float32 coefficients instead of
+ * K-TanH's three small integers.  Coefficients are formed in double precision
+ * and rounded to Float32; |x| - a_t is exact in Float32; the polynomial is
+ * evaluated by Horner's scheme in Float32 with one rounding per operation;
+ * BFloat16 in and out (round to nearest even), the sign put back at the end,
+ * a NaN returned quieted.  Parity unpinned by the paper: Table 2's figures for
+ * these rows (0.43e-2 / 0.04e-2 maximum error, 28.57 % relative error) are not
+ * reached by this reading, which is far more accurate; pinned by the remainder
+ * bound of Taylor's theorem, by the midpoints (where T_n = TanH), and by the
+ * regions. */
+void oracle_taylor_coefficients(float *c /* [32][4]: entry t, powers 0..3 */)
+{
+    for (int e = -2; e <= 1; ++e) {
+        for (int m = 0; m < 8; ++m) {
+            int t = (((e + 127) & 3) << 3) | m;         /* Table 1's index of the interval */
+            double a = ldexp(1.0 + (m + 0.5) / 8.0, e); /* midpoint of [2^e (1 + m/8), 2^e (1 + (m+1)/8)) */
+            double f0 = tanh(a);
+            double f1 = 1.0 - f0 * f0;                  /* first derivative */
+            double f2 = -2.0 * f0 * f1;                 /* second: D(1 - f^2) = -2 f Df */
+            double f3 = -2.0 * (f1 * f1 + f0 * f2);     /* third: -2 (Df Df + f DDf) */
+            c[4 * t + 0] = (float)f0;
+            c[4 * t + 1] = (float)f1;
+            c[4 * t + 2] = (float)(f2 / 2.0);
+            c[4 * t + 3] = (float)(f3 / 6.0);
+        }
+    }
+}
+
+static void ktaylor(const uint16_t *in, uint16_t *out, size_t n, int degree)
+{
+    float c[32 * 4];
+    oracle_taylor_coefficients(c);
+    for (size_t i = 0; i < n; ++i) {
+        uint16_t x = in[i];
+        unsigned mag = x & 0x7FFFu;
+        unsigned cond = mag >> 4; /* 8 exponent bits, 3 mantissa bits */
+        if (mag > 0x7F80u) { out[i] = (uint16_t)(x | 0x0040u); continue; }
+        if (cond < ((125u << 3) | 0u)) { out[i] = x; continue; }
+        if (cond > ((128u << 3) | 7u)) { out[i] = (uint16_t)((x & 0x8000u) | 0x3F80u); continue; }
+        unsigned t = cond & 31u;
+        float a_t = widen((uint16_t)((mag & 0x7FF0u) | 0x0008u)); /* the interval's midpoint */
+        float h = widen((uint16_t)mag) - a_t;
+        const float *ct = c + 4 * t;
+        float p = ct[degree];
+        for (int k = degree - 1; k >= 0; --k) {
+            p = p * h;
+            p = p + ct[k];
+        }
+        out[i] = with_sign_of(x, p);
+    }
+}
+
+void oracle_ktaylor2(const uint16_t *in, uint16_t *out, size_t n) { ktaylor(in, out, n, 2); }
+void oracle_ktaylor3(const uint16_t *in, uint16_t *out, size_t n) { ktaylor(in, out, n, 3); }
 
 /* ------------------------------------------------------------------ */
 /* The six base operations once more under the names and argument lists of the

@@ -126,6 +126,11 @@ def _load():
             getattr(lib, name).restype = None
         lib.oracle_pade_coefficients.argtypes = [ctypes.c_int, vp, vp]
         lib.oracle_pade_coefficients.restype = None
+        for name in ("oracle_ktaylor2", "oracle_ktaylor3"):
+            getattr(lib, name).argtypes = [vp, vp, sz]
+            getattr(lib, name).restype = None
+        lib.oracle_taylor_coefficients.argtypes = [vp]
+        lib.oracle_taylor_coefficients.restype = None
         lp64 = ctypes.POINTER(OracleLut64)
         lib.oracle_fit_lut64.argtypes = [lp64]
         for name in ("oracle_ktanh64_bf16", "oracle_ktanh64_f32", "oracle_ksigmoid64", "oracle_kswish64",
@@ -342,6 +347,23 @@ def pade_coefficients(which):
     num, den = np.zeros(p + 1), np.zeros(q + 1)
     _load().oracle_pade_coefficients(which, num.ctypes.data, den.ctypes.data)
     return num.tolist(), den.tolist()
+
+
+def ktaylor2(x_bits):
+    """Piecewise Taylor polynomial of degree 2 about the midpoints of K-TanH's intervals, BFloat16 bits."""
+    return _pade("oracle_ktaylor2", x_bits)
+
+
+def ktaylor3(x_bits):
+    """The same of degree 3."""
+    return _pade("oracle_ktaylor3", x_bits)
+
+
+def taylor_coefficients():
+    """[32, 4] Float32: for Table 1's index t, the coefficients of (|x| - a_t)^0 .. ^3."""
+    c = np.zeros((32, 4), dtype=np.float32)
+    _load().oracle_taylor_coefficients(c.ctypes.data)
+    return c
 
 
 def _backward(name, dy_bits, fwd_bits):

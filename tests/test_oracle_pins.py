@@ -900,6 +900,73 @@ def test_pade_approximants(oracle):
     assert 1.8e-2 < e32.max() <= 2.35e-2 and np.max(e32[t != 0] / np.abs(t[t != 0])) <= 2.59e-2
 
 
+def test_taylor_rows(oracle):
+    """The two Taylor rows of Table 2 under the stated reading (piecewise about the midpoints of
+    K-TanH's 32 intervals).  The coefficients against a power-series solution of y' = 1 - y^2 in
+    40-digit decimal arithmetic; the polynomial against Taylor's remainder bound; the midpoints, where
+    the polynomial is TanH itself; values that any approximant this accurate must round to; the
+    regions, NaN and odd symmetry; and what Table 2 prints for these rows, which this reading does
+    not reproduce."""
+    from decimal import Decimal as D, getcontext
+    getcontext().prec = 40
+    coeff = oracle.taylor_coefficients()
+    assert coeff.shape == (32, 4) and coeff.dtype == np.float32
+    seen = set()
+    for e in (-2, -1, 0, 1):
+        for m in range(8):
+            t = (((e + 127) & 3) << 3) | m
+            seen.add(t)
+            a = D(2) ** e * (D(1) + (D(m) + D("0.5")) / D(8))
+            big = (2 * a).exp()
+            c = [(big - 1) / (big + 1)]                                 # y(a) = TanH(a)
+            for n in range(3):                                          # (n + 1) c[n+1] = [n = 0] - (y^2)_n
+                c.append(((1 if n == 0 else 0) - sum(c[k] * c[n - k] for k in range(n + 1))) / (n + 1))
+            want = np.array([float(v) for v in c]).astype(np.float32)
+            assert np.array_equal(coeff[t], want), (t, coeff[t], want)
+    assert seen == set(range(32))
+
+    x = np.arange(0x3E80, 0x4080, dtype=np.uint16)                      # [0.25, 4): the table's range
+    xv = _bf16_val(x)
+    t = (x >> 4) & 31
+    mid = _bf16_val((x & 0x7FF0) | 0x0008)
+    h = xv - mid
+    c64 = coeff.astype(np.float64)[t]
+    p2 = c64[:, 0] + h * (c64[:, 1] + h * c64[:, 2])
+    p3 = p2 + c64[:, 3] * h ** 3
+    tanh = np.tanh(xv)
+    # Taylor's theorem (the third derivative of TanH is at most 2 in magnitude, the fourth below 4.09),
+    # plus the Float32 rounding of the coefficients
+    assert np.all(np.abs(p2 - tanh) <= 2.0 * np.abs(h) ** 3 / 6 + 1.5e-7)
+    assert np.all(np.abs(p3 - tanh) <= 4.09 * h ** 4 / 24 + 1.5e-7)
+    # a wrong last coefficient would break the bound: it moves the value by far more than the bound's slack
+    assert np.max(np.abs(c64[:, 3] * h ** 3)) > 2e-5 and np.max(np.abs(c64[:, 2] * h ** 2)) > 5e-4
+    # this reading's maximum errors before the result is rounded to BFloat16; Table 2 prints 0.43e-2 and 0.04e-2
+    assert 6e-5 < np.abs(p2 - tanh).max() < 8e-5 and 3e-6 < np.abs(p3 - tanh).max() < 5e-6
+
+    for fn, want in ((oracle.ktaylor2, p2), (oracle.ktaylor3, p3)):
+        got = fn(x)
+        d = _ulp_distance_bf16(got, _round_f64_to_bf16(want))
+        assert d.max() <= 1 and np.mean(d == 0) > 0.99                  # Float32 Horner against float64
+        assert np.array_equal(fn(x ^ 0x8000), got ^ 0x8000)
+        mids = np.unique((x & 0x7FF0) | 0x0008).astype(np.uint16)
+        assert mids.size == 32 and np.array_equal(fn(mids), _round_f64_to_bf16(np.tanh(_bf16_val(mids))))
+        one = lambda bits: int(fn(np.array([bits], np.uint16))[0])
+        # TanH(1) = 0.761594 -> 0x3F43, TanH(0.5) = 0.462117 -> 0x3EED, TanH(2) = 0.964028 -> 0x3F77, TanH(3.875) = 0.99914 -> 1.0
+        assert one(0x3F80) == 0x3F43 and one(0x3F00) == 0x3EED and one(0x4000) == 0x3F77 and one(0xC000) == 0xBF77
+        assert one(0x4078) == 0x3F80
+        below = np.arange(0, 0x3E80, dtype=np.uint16)
+        assert np.array_equal(fn(below), below) and np.array_equal(fn(below | 0x8000), below | 0x8000)
+        beyond = np.arange(0x4080, 0x7F81, dtype=np.uint16)
+        assert np.all(fn(beyond) == 0x3F80) and np.all(fn(beyond | 0x8000) == 0xBF80)
+        assert one(0x7FC1) == 0x7FC1 and one(0xFF81) == 0xFFC1 and one(0x7F81) == 0x7FC1
+        allx = _finite_bf16()
+        err = np.abs(_bf16_val(fn(allx)) - np.tanh(_bf16_val(allx)))
+        # the largest error is the pass-through region's, x - TanH(x) just below 0.25, as for K-TanH itself
+        assert abs(err.max() - 5.023e-3) < 1e-6 and int(allx[np.argmax(err)]) & 0x7FFF == 0x3E7F
+        inside = ((allx & 0x7FFF) >= 0x3E80)
+        assert err[inside].max() <= 2.0 ** -9 + 1e-4                    # half a BFloat16 step below 1, plus the polynomial's own error
+
+
 def test_checksums_against_an_independent_implementation(oracle):
     """All 65,536 outputs of the four BFloat16 operations, as CRC32, against values recorded from
     an implementation that shares nothing with this oracle."""
