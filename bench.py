@@ -257,6 +257,9 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
     for name in ("kpade32_bf16", "kpade78_bf16"):
         record(name, "Table 2's rational approximant (Float32 arithmetic with a division) on the headline tensor, 8 rotating pairs",
                lambda i, fn=getattr(binding, name): fn(xs[i % ROTATE], out=ys[i % ROTATE]), n2, 4, 1000, 200)
+    for name in ("ktaylor2_bf16", "ktaylor3_bf16"):
+        record(name, "piecewise Taylor polynomial on K-TanH's 32 intervals (3 or 4 Float32 coefficients per table read) on the headline tensor, 8 rotating pairs",
+               lambda i, fn=getattr(binding, name): fn(xs[i % ROTATE], out=ys[i % ROTATE]), n2, 4, 1000, 200)
     record("ktanh_bf16_backward", "dy, y and dx as the headline tensor (6 B per element), 8 rotating triples",
            lambda i: binding.ktanh_bf16_backward(xs[i % ROTATE], ys[(i + 1) % ROTATE], dx=ys[i % ROTATE]),
            n2, 6, 1000, 200)
@@ -271,7 +274,8 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
         x4.append(x4[0].roll(k * 4099))
     y4 = [torch.empty_like(t) for t in x4]
     n4 = x4[0].numel()
-    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16"):
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16", "ktaylor2_bf16",
+                 "ktaylor3_bf16"):
         fn = getattr(binding, name)
         record(f"{name}_mlp", "[8192,16384] bf16 ~ N(0,1), seed 190904, 4 rotating buffer pairs",
                lambda i, fn=fn: fn(x4[i % 4], out=y4[i % 4]), n4, 4, 200, 60)
@@ -334,7 +338,7 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
         rec[key] /= T
     record("klstm_cell_fused_T64", "same shapes, 3 rotating gate/h buffers; one call carries c through all 64 steps",
            lambda i: binding.klstm_cell(gates_rot[i % 3], c0, c_out=c, h_out=h_rot[i % 3]), cells * T,
-           10 + 8.0 / T, 90, 30)
+           10 + 8.0 / T, 400, 200)  # long enough for the clocks to settle after the launch-bound graph replays
     return out
 
 
@@ -462,7 +466,8 @@ def run_probe(torch, binding, probe, wl, upload, headline):
         x4.append(x4[0].roll(k * 4099))
     y4 = [torch.empty_like(t) for t in x4]
     sink = torch.zeros(512, dtype=torch.int16, device=x4[0].device)
-    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16"):
+    for name in ("ktanh_bf16", "ksigmoid", "kswish", "kgelu", "kpade32_bf16", "kpade78_bf16", "ktaylor2_bf16",
+                 "ktaylor3_bf16"):
         for k in range(20):
             getattr(binding, name)(x4[k % 4], out=y4[k % 4])
     for k in range(20):

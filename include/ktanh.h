@@ -266,6 +266,21 @@ ktanh_status_t klstm_cell_backward(const uint16_t *gates, const float *c_prev, c
 ktanh_status_t kpade32_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
 ktanh_status_t kpade78_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
 
+/* Table 2's rows "Taylor approx degree 2" and "degree 3".  The paper names the method (Section 1) and
+ * prints two error figures per row, but neither partition nor expansion point.  Built here on
+ * K-TanH's own terms: the regions of Algorithm 1 (|x| below T1 = 0.25 is returned as it is, |x| from
+ * 4.0 on gives +-1) and, in between, the 32 intervals that Table 1's index t names (2 low exponent
+ * bits, 3 high mantissa bits); on each the Taylor polynomial of TanH of that degree about the
+ * interval's midpoint a_t, sum_k TanH^(k)(a_t)/k! (|x| - a_t)^k.  A table entry is thus 3 or 4 Float32
+ * coefficients (formed in double precision, then rounded) in place of K-TanH's three small integers.
+ * BFloat16 in and out, n elements each, device; Float32 arithmetic, Horner's scheme, one rounding per
+ * operation, the sign put back, the result rounded to nearest even; a NaN is returned quieted.  The
+ * table is fixed: there is no table argument.  This reading is far more accurate than the figures
+ * Table 2 prints for these rows (its error is that of the BFloat16 result, half a step).
+ * Same conventions (alignment, aliasing, sizes, errors) as ktanh_bf16. */
+ktanh_status_t ktaylor2_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
+ktanh_status_t ktaylor3_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream);
+
 /* The gradients that read a table, with a 64-interval table (Section 2.4, last paragraph) inside:
  * the same formulas and operation order with K = ktanh64_bf16 (ktanh64_f32 on Float32 tensors).
  * `lut` == NULL selects the fitted 64-interval table.  (ktanh_bf16_backward, ksigmoid_backward and

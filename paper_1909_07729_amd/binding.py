@@ -36,6 +36,7 @@ SIGNATURES = {
     "kswish64_f32_backward": "pppnLs", "kgelu64_f32_backward": "pppnLs",
     "klstm_cell_backward": "ppppppnnls", "klstm_cell64_backward": "ppppppnnLs",
     "kpade32_bf16": "ppns", "kpade78_bf16": "ppns",
+    "ktaylor2_bf16": "ppns", "ktaylor3_bf16": "ppns",
 }
 EXPORTS = tuple(SIGNATURES)
 
@@ -218,6 +219,16 @@ def kpade32_bf16(x, out=None, stream=None):
 def kpade78_bf16(x, out=None, stream=None):
     """The Pade[7/8] approximant of TanH (a comparison row of the paper's Table 2) on BFloat16."""
     return _pade("kpade78_bf16", x, out, stream)
+
+
+def ktaylor2_bf16(x, out=None, stream=None):
+    """Piecewise Taylor polynomials of degree 2 on K-TanH's intervals (a comparison row of Table 2)."""
+    return _pade("ktaylor2_bf16", x, out, stream)
+
+
+def ktaylor3_bf16(x, out=None, stream=None):
+    """The same of degree 3."""
+    return _pade("ktaylor3_bf16", x, out, stream)
 
 
 def ktanh_f32(x, out=None, lut=None, stream=None):

@@ -251,7 +251,11 @@ __device__ __forceinline__ void store_stream(uint32_t *base, unsigned byte_offse
 // OP_COPY moves the data unchanged: the same accesses with no arithmetic, the yardstick for what the
 // memory system allows in this launch shape.
 // OP_PADE32 / OP_PADE78: the rational approximants of Section 2 that Table 2 compares K-TanH with.
-enum Op { OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_COPY = 4, OP_PADE32 = 5, OP_PADE78 = 6 };
+// OP_TAYLOR2 / OP_TAYLOR3: piecewise Taylor polynomials on K-TanH's own intervals, for Table 2's Taylor rows.
+enum Op {
+    OP_TANH = 0, OP_SIGMOID = 1, OP_SWISH = 2, OP_GELU = 3, OP_COPY = 4, OP_PADE32 = 5, OP_PADE78 = 6,
+    OP_TAYLOR2 = 7, OP_TAYLOR3 = 8
+};
 
 // Pade[3/2] = x (15 + x^2) / (15 + 6 x^2) on min(|x|, 4), capped at 1;
 // Pade[7/8] = x (2027025 + 270270 x^2 + 6930 x^4 + 36 x^6) / (2027025 + 945945 x^2 + 51975 x^4 + 630 x^6 + x^8)
@@ -291,14 +295,87 @@ __device__ __forceinline__ uint32_t pade_pair(uint32_t w)
     return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
 }
 
+// The coefficient table of the Taylor polynomials, spread over the lanes like the K-TanH table: lane
+// l holds the four coefficients of interval l & 31 (both halves of the wavefront hold all 32).
+struct TaylorLane {
+    float c[4];
+    __device__ __forceinline__ explicit TaylorLane(const KtTaylorPack &pack)
+    {
+        const unsigned t = threadIdx.x & 31;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) c[k] = pack.c[k][t];
+    }
+    // Coefficient k of the interval named by bits [6:2] of the byte address (bit 7 picks one of the
+    // two lanes that hold it, higher bits are ignored).  Every lane of the wavefront must be enabled.
+    __device__ __forceinline__ float get(int k, uint32_t t_times_4) const
+    {
+        return __uint_as_float(
+            (uint32_t)__builtin_amdgcn_ds_bpermute((int)t_times_4, (int)__float_as_uint(c[k])));
+    }
+};
+
+// T_n(|x|) = sum_k c_k (|x| - a_t)^k for one BFloat16 magnitude in [0.25, 4) (bits 0..15 of `mag`);
+// anything for magnitudes outside.  Float32, Horner's scheme, one rounding per operation.  The
+// interval's midpoint a_t is the magnitude with its four low mantissa bits replaced by 1000, and
+// the difference is exact.
+template <int DEGREE>
+__device__ __forceinline__ float taylor_of_magnitude(uint32_t mag, const TaylorLane &tab)
+{
+    const uint32_t at = mag >> 2;  // bits [6:2] <- bits [8:4] of the magnitude: t
+    const float h = __uint_as_float(mag << 16) - __uint_as_float(((mag & 0x7FF0u) | 0x0008u) << 16);
+    float p = tab.get(DEGREE, at);
+#pragma unroll
+    for (int k = DEGREE - 1; k >= 0; --k) {
+        p = p * h;
+        p = p + tab.get(k, at);
+    }
+    return p;
+}
+
+// Both halves of w: the regions of Algorithm 1 (pass-through below 0.25, 1 from 4.0 on), the
+// polynomial in between, signs put back, NaNs returned quieted.
+template <int OP>
+__device__ __forceinline__ uint32_t taylor_pair(uint32_t w, const TaylorLane &tab)
+{
+    constexpr int DEGREE = OP == OP_TAYLOR3 ? 3 : 2;
+    const uint32_t mag2 = w & kMag2;
+    const uint32_t y2 = narrow_pair(taylor_of_magnitude<DEGREE>(mag2 & 0xFFFFu, tab),
+                                    taylor_of_magnitude<DEGREE>(mag2 >> 16, tab));
+    const uint32_t pass = sign_mask_pair(as_u32(as_i16x2(mag2) - as_i16x2(0x3E803E80u)));
+    const uint32_t beyond = sign_mask_pair(as_u32(as_i16x2(0x407F407Fu) - as_i16x2(mag2)));
+    uint32_t res = bitsel(pass, mag2, y2);
+    res = bitsel(beyond, 0x3F803F80u, res);
+    res = bitsel(kMag2, res, w);
+    return bitsel(nan_mask_pair(mag2), w | 0x00400040u, res);
+}
+
+// The kernel-argument form and the per-lane form of the table an operation reads.
+template <int OP>
+struct TableOf {
+    typedef KtLutPack Pack;
+    typedef LaneTable Lane;
+};
+template <>
+struct TableOf<OP_TAYLOR2> {
+    typedef KtTaylorPack Pack;
+    typedef TaylorLane Lane;
+};
+template <>
+struct TableOf<OP_TAYLOR3> {
+    typedef KtTaylorPack Pack;
+    typedef TaylorLane Lane;
+};
+
 // WIDE selects the 64-interval table layout.
-template <int OP, bool WIDE = false>
-__device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
+template <int OP, bool WIDE = false, class Tab>
+__device__ __forceinline__ uint32_t apply_pair(uint32_t w, const Tab &tab)
 {
     if constexpr (OP == OP_COPY) {
         return w;
     } else if constexpr (OP == OP_PADE32 || OP == OP_PADE78) {
         return pade_pair<OP>(w);
+    } else if constexpr (OP == OP_TAYLOR2 || OP == OP_TAYLOR3) {
+        return taylor_pair<OP>(w, tab);
     } else if constexpr (OP == OP_TANH) {
         return ktanh_pair<true, WIDE>(w, tab);
     } else if constexpr (OP == OP_SIGMOID) {
@@ -327,8 +404,8 @@ __device__ __forceinline__ uint32_t apply_pair(uint32_t w, const LaneTable &tab)
     }
 }
 
-template <int OP, bool WIDE = false>
-__device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const LaneTable &tab)
+template <int OP, bool WIDE = false, class Tab>
+__device__ __forceinline__ uint4 apply_vec_bf16(uint4 v, const Tab &tab)
 {
     return uint4{apply_pair<OP, WIDE>(v.x, tab), apply_pair<OP, WIDE>(v.y, tab),
                  apply_pair<OP, WIDE>(v.z, tab), apply_pair<OP, WIDE>(v.w, tab)};

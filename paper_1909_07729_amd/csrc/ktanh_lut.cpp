@@ -1,6 +1,8 @@
 // Host side of libktanh: the paper's parameter table, its validation and its kernel-argument form.
 #include "ktanh_pack.h"
 
+#include <cmath>
+
 namespace {
 
 // Table 1 (optimised parameters for BFloat16 inputs), stored by integer index
@@ -162,4 +164,20 @@ ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack, boo
 ktanh_status_t kt_pack_lut64_f32(const ktanh_lut64_t *lut, KtLutPack *pack)
 {
     return pack_slots64(lut, pack, false);
+}
+
+// With y = TanH(a), the derivatives of TanH at a over k! are:  1 - y^2,  -y (1 - y^2),
+// -(1 - y^2)(1 - 3 y^2) / 3.
+void kt_pack_taylor(KtTaylorPack *pack)
+{
+    for (int t = 0; t < 32; ++t) {
+        const int exponent = ((t >> 3) + 3) % 4 - 2;  // t >> 3 is E & 3 for E = 125..128, i.e. 2^-2..2^1
+        const double a = std::ldexp(1.0 + ((t & 7) + 0.5) / 8.0, exponent);
+        const double y = std::tanh(a);
+        const double slope = 1.0 - y * y;
+        pack->c[0][t] = (float)y;
+        pack->c[1][t] = (float)slope;
+        pack->c[2][t] = (float)(-(y * slope));
+        pack->c[3][t] = (float)(-(slope * (1.0 - 3.0 * (y * y))) / 3.0);
+    }
 }

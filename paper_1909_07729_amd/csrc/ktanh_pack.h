@@ -30,3 +30,12 @@ ktanh_status_t kt_pack_lut_f32(const ktanh_lut_t *lut, KtLutPack *pack);
 ktanh_status_t kt_pack_lut64_bf16(const ktanh_lut64_t *lut, KtLutPack *pack,
                                   bool *within_unit = nullptr);
 ktanh_status_t kt_pack_lut64_f32(const ktanh_lut64_t *lut, KtLutPack *pack);
+
+// The piecewise Taylor polynomials of TanH that stand in for Table 2's two Taylor rows: for each of
+// Table 1's 32 intervals (index t = 2 low exponent bits, 3 high mantissa bits of |x| in [0.25, 4))
+// the coefficients of (|x| - a_t)^k, k = 0..3, about the interval's midpoint a_t, formed in double
+// precision and rounded to Float32.  c[k][t].
+struct KtTaylorPack {
+    float c[4][32];
+};
+void kt_pack_taylor(KtTaylorPack *pack);

@@ -197,3 +197,13 @@ extern "C" ktanh_status_t kpade78_bf16(const uint16_t *in, uint16_t *out, size_t
 {
     return launch_elementwise<false, OP_PADE78>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
 }
+
+extern "C" ktanh_status_t ktaylor2_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TAYLOR2>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
+}
+
+extern "C" ktanh_status_t ktaylor3_bf16(const uint16_t *in, uint16_t *out, size_t n, ktanh_stream_t stream)
+{
+    return launch_elementwise<false, OP_TAYLOR3>(in, out, n, static_cast<const ktanh_lut_t *>(nullptr), stream);
+}

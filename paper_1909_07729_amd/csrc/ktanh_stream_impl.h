@@ -30,8 +30,8 @@ struct EdgeArgs {
     unsigned n_head;
 };
 
-template <bool F32, int OP, bool WIDE>
-__device__ __forceinline__ uint4 apply_vec(uint4 v, const LaneTable &tab)
+template <bool F32, int OP, bool WIDE, class Tab>
+__device__ __forceinline__ uint4 apply_vec(uint4 v, const Tab &tab)
 {
     if constexpr (F32) return apply_vec_f32<OP, WIDE>(v, tab);
     else return apply_vec_bf16<OP, WIDE>(v, tab);
@@ -44,9 +44,9 @@ __global__ __launch_bounds__(kBlock) void stream_kernel(const uint4 *vin, uint4 
                                                         unsigned long long nvec, unsigned skew,
                                                         unsigned n_edge /* head + tail, < 64 */,
                                                         unsigned whole, unsigned lg_seg,  // TileOrder
-                                                        EdgeArgs edge, KtLutPack pack)
+                                                        EdgeArgs edge, typename TableOf<OP>::Pack pack)
 {
-    const LaneTable tab(pack);
+    const typename TableOf<OP>::Lane tab(pack);
 
     // One vector per lane, one tile of kBlock vectors per block, no loop: fresh blocks keep loads and
     // stores of different tiles overlapped, which a grid-stride loop over the same tiles does not
@@ -96,6 +96,13 @@ inline ktanh_status_t pack_for(const ktanh_lut64_t *lut, bool f32, KtLutPack *pa
     return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
 }
 
+// The Taylor polynomials have one fixed table; the caller's table argument is not used.
+inline ktanh_status_t pack_for(const ktanh_lut_t *, bool, KtTaylorPack *pack)
+{
+    kt_pack_taylor(pack);
+    return KT_OK;
+}
+
 template <bool F32, int OP, class Lut>
 ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut *lut,
                                   ktanh_stream_t stream)
@@ -108,7 +115,7 @@ ktanh_status_t launch_elementwise(const void *in, void *out, size_t n, const Lut
     const uintptr_t ain = reinterpret_cast<uintptr_t>(in), aout = reinterpret_cast<uintptr_t>(out);
     if (ain % kElem != 0 || aout % kElem != 0) return KT_ERR_ALIGN;
     if (n > (size_t)1 << 40) return KT_ERR_SHAPE;  // keeps the grid below 2^31 blocks
-    KtLutPack pack;
+    typename TableOf<OP>::Pack pack;
     const ktanh_status_t st = pack_for(lut, F32, &pack);
     if (st != KT_OK) return st;
 

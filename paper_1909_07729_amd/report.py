@@ -8,7 +8,7 @@ input goes through the GPU kernel and the result is compared with TanH in double
 derived Sigmoid, Swish and GELU are compared with their exact forms on |x| <= 16.  Throughput is
 taken on a [50, 128, 4096] BFloat16 tensor.  (The ablation's row shows the two error figures that
 Table 2 of the paper prints for K-TanH, 1.67e-2 and 3.03 %.)  The rational Pade approximants of
-Section 2, which Table 2 compares K-TanH with, are measured the same way.  The reference values are numpy's,
+Section 2 and the piecewise Taylor polynomials, which stand for rows of Table 2, are measured the same way.  The reference values are numpy's,
 computed here; the library's arithmetic is not repeated on the CPU.
 """
 from __future__ import annotations
@@ -76,15 +76,18 @@ def error_rows() -> list[dict]:
 
 
 def comparator_rows() -> list[dict]:
-    """The rational Pade approximants that Table 2 of the paper sets against K-TanH: the same error
-    figures and throughput, measured with this library's kernels."""
+    """The approximants that Table 2 of the paper sets against K-TanH and that this library builds
+    (the rational Pade approximants; piecewise Taylor polynomials on K-TanH's intervals for the Taylor
+    rows): the same error figures and throughput, measured with this library's kernels."""
     bits = wl.all_bf16_patterns()
     bits = bits[(bits & 0x7FFF) < 0x7F80]
     x = _values(bits)
     want = np.tanh(x)
     nz = want != 0
     rows = []
-    for name, fn in (("Pade[3/2]", binding.kpade32_bf16), ("Pade[7/8]", binding.kpade78_bf16)):
+    for name, fn in (("Pade[3/2]", binding.kpade32_bf16), ("Pade[7/8]", binding.kpade78_bf16),
+                     ("Taylor degree 2, 32 intervals", binding.ktaylor2_bf16),
+                     ("Taylor degree 3, 32 intervals", binding.ktaylor3_bf16)):
         err = np.abs(_values(_on_gpu(fn, bits)) - want)
         rows.append({"approximant": name, "max_abs": float(err.max()), "at": f"0x{int(bits[int(np.argmax(err))]):04X}",
                      "max_rel": float(np.max(err[nz] / np.abs(want[nz]))), "elements_per_s": _throughput(fn)})
@@ -126,7 +129,7 @@ def main() -> None:
         print(f"{r['table']:36s} {r['max_abs']:9.5f} {r['at']:>7s} {100 * r['max_rel']:7.2f}% "
               f"{r['mean_abs_region']:18.5f} {r['elements_per_s'] / 1e9:9.1f}")
     print()
-    print("Table 2's rational approximants (Float32 arithmetic, BFloat16 in and out) against TanH (double)")
+    print("Table 2's comparison approximants (Float32 arithmetic, BFloat16 in and out) against TanH (double)")
     print(f"{'approximant':36s} {'max abs':>9s} {'at':>7s} {'max rel':>8s} {'Gelem/s':>9s}")
     for r in comparator_rows():
         print(f"{r['approximant']:36s} {r['max_abs']:9.5f} {r['at']:>7s} {100 * r['max_rel']:7.2f}% "

@@ -979,6 +979,7 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
         yb, sb = oracle.ktanh_bf16(xb), oracle.ksigmoid(xb)
         cases = {
             "kpade32_bf16": ("bf16", oracle.kpade32(xb)), "kpade78_bf16": ("bf16", oracle.kpade78(xb)),
+            "ktaylor2_bf16": ("bf16", oracle.ktaylor2(xb)), "ktaylor3_bf16": ("bf16", oracle.ktaylor3(xb)),
             "ktanh_bf16": ("bf16", yb), "ksigmoid": ("bf16", sb), "kswish": ("bf16", oracle.kswish(xb)),
             "kgelu": ("bf16", oracle.kgelu(xb)), "ktanh64_bf16": ("bf16", oracle.ktanh64_bf16(xb)),
             "ksigmoid64": ("bf16", oracle.ksigmoid64(xb)), "kswish64": ("bf16", oracle.kswish64(xb)),
@@ -1048,14 +1049,16 @@ def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, ora
 
 
 # ------------------------------------------------------------------ Table 2's comparison approximants
-def test_pade_comparators(gpu, oracle):
-    """kpade32_bf16 and kpade78_bf16 against the oracle, bit for bit (same Float32 operations in the
-    same order, correctly rounded division on both sides): every BFloat16 pattern, a ragged sample of
-    the transformer-MLP tensor at an odd offset, in place."""
+def test_table2_comparators(gpu, oracle):
+    """kpade32_bf16, kpade78_bf16, ktaylor2_bf16 and ktaylor3_bf16 against the oracle, bit for bit
+    (same Float32 operations in the same order, correctly rounded division on both sides, the Taylor
+    coefficients formed separately on each side): every BFloat16 pattern, a ragged sample of the
+    transformer-MLP tensor at an odd offset, in place."""
     binding, torch = gpu
     x = np.concatenate([wl.all_bf16_patterns(), wl.mlp_preactivations(100003, seed=86)])
     xd = _to_dev(torch, x)
-    for name, ref in (("kpade32_bf16", oracle.kpade32), ("kpade78_bf16", oracle.kpade78)):
+    for name, ref in (("kpade32_bf16", oracle.kpade32), ("kpade78_bf16", oracle.kpade78),
+                      ("ktaylor2_bf16", oracle.ktaylor2), ("ktaylor3_bf16", oracle.ktaylor3)):
         want = ref(x)
         assert np.array_equal(_to_host(getattr(binding, name)(xd), np.uint16), want), name
         n = 50021
@@ -1087,8 +1090,9 @@ def test_accuracy_report_figures_equal_the_oracle_s(gpu, oracle):
     assert rows[0]["max_abs"] < rows[1]["max_abs"] < rows[2]["max_abs"]
     assert rows[1]["mean_abs_region"] < rows[0]["mean_abs_region"] < rows[2]["mean_abs_region"]
     comp = report.comparator_rows()
-    assert [r["approximant"] for r in comp] == ["Pade[3/2]", "Pade[7/8]"]
-    for row, ref in zip(comp, (oracle.kpade32, oracle.kpade78)):
+    assert [r["approximant"] for r in comp] == ["Pade[3/2]", "Pade[7/8]", "Taylor degree 2, 32 intervals",
+                                                "Taylor degree 3, 32 intervals"]
+    for row, ref in zip(comp, (oracle.kpade32, oracle.kpade78, oracle.ktaylor2, oracle.ktaylor3)):
         err = np.abs(wl.bf16_bits_to_f32(ref(bits)).astype(np.float64) - np.tanh(x))
         assert row["max_abs"] == float(err.max()) and row["elements_per_s"] > 1e11
     derived = report.derived_rows()
