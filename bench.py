@@ -339,6 +339,9 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
     record("klstm_cell_fused_T64", "same shapes, 3 rotating gate/h buffers; one call carries c through all 64 steps",
            lambda i: binding.klstm_cell(gates_rot[i % 3], c0, c_out=c, h_out=h_rot[i % 3]), cells * T,
            10 + 8.0 / T, 400, 200)  # long enough for the clocks to settle after the launch-bound graph replays
+    # the launch of the fused kernel with its arithmetic taken out, on the same buffers
+    record("probe_lstm_T64", "ktanh_probe_lstm: the loads, stores, waits and loop of klstm_cell_fused_T64 with no arithmetic, same buffers",
+           lambda i: probe.ktanh_probe_lstm(gates_rot[i % 3], c0, c, h_rot[i % 3]), cells * T, 10 + 8.0 / T, 400, 200)
     return out
 
 
@@ -508,6 +511,8 @@ def run_probe(torch, binding, probe, wl, upload, headline):
         binding.klstm_cell(gates_rot[k % 3], c0, c_out=c, h_out=h_rot[k % 3])
     for t in range(24):
         binding.klstm_cell(gates[t:t + 1], c0, c_out=c, h_out=h_rot[0][t:t + 1])
+    for k in range(21):
+        probe.ktanh_probe_lstm(gates_rot[k % 3], c0, c, h_rot[k % 3])
     dh = torch.zeros((c0.shape[0], c0.shape[1]), dtype=gates.dtype, device=gates.device)
     dc_next = torch.ones_like(c0)
     for t in range(24):

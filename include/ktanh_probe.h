@@ -30,6 +30,13 @@ ktanh_status_t ktanh_probe_read(const void *in, void *sink, size_t n_bytes, ktan
  * out: device, 1 KiB aligned, n_bytes a multiple of 16. */
 ktanh_status_t ktanh_probe_write(void *out, size_t n_bytes, ktanh_stream_t stream);
 
+/* The launch of klstm_cell with the arithmetic taken out: the same loads (four gate words per lane
+ * and step, prefetched the same number of steps ahead), stores, waits and loop.  Output word (t, b, j)
+ * of h_out, taken as 32 bits over two neighbouring cells, is the XOR of the step's four gate words
+ * and the bits of c_in[b][2j]; c_out = c_in.  Arguments, shapes, alignment and errors as klstm_cell. */
+ktanh_status_t ktanh_probe_lstm(const uint16_t *gates, const float *c_in, float *c_out,
+                                uint16_t *h_out, size_t T, size_t B, size_t H, ktanh_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

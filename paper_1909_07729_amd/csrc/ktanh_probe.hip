@@ -1,8 +1,10 @@
 // libktanh_probe: measurement yardsticks, not operations of the paper.  Each is the launch of the
 // element-wise entry points (one wavefront per block, one 128-bit vector per lane, the same load and
 // store policies) with the arithmetic, the stores or the loads taken out, so that a benchmark can
-// put what the memory system allows for this launch shape next to the K-TanH figures.
+// put what the memory system allows for this launch shape next to the K-TanH figures.  Likewise the
+// launch of the fused LSTM-cell kernel with its arithmetic taken out.
 #include "ktanh_probe.h"
+#include "ktanh_lstm_impl.h"
 #include "ktanh_stream_impl.h"
 
 using namespace ktanh_device;
@@ -66,4 +68,12 @@ extern "C" ktanh_status_t ktanh_probe_write(void *out, size_t n_bytes, ktanh_str
     if (st != KT_OK) return st;
     return launch_checked(write_kernel, (unsigned)tiles, kBlock, stream, static_cast<uint4 *>(out),
                           (unsigned long long)(n_bytes / 16));
+}
+
+extern "C" ktanh_status_t ktanh_probe_lstm(const uint16_t *gates, const float *c_in, float *c_out,
+                                           uint16_t *h_out, size_t T, size_t B, size_t H,
+                                           ktanh_stream_t stream)
+{
+    return launch_cell<false, false>(gates, c_in, c_out, h_out, T, B, H,
+                                     static_cast<const ktanh_lut_t *>(nullptr), stream);
 }

@@ -11,7 +11,8 @@ from .binding import KtanhError, _BF16_VIEWS, _check, _stream_handle
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libktanh_probe.so")
-SIGNATURES = {"ktanh_probe_copy": "ppns", "ktanh_probe_read": "ppns", "ktanh_probe_write": "pns"}
+SIGNATURES = {"ktanh_probe_copy": "ppns", "ktanh_probe_read": "ppns", "ktanh_probe_write": "pns",
+              "ktanh_probe_lstm": "ppppnnns"}
 EXPORTS = tuple(SIGNATURES)
 
 _lib = None
@@ -65,3 +66,23 @@ def ktanh_probe_write(out: torch.Tensor, stream=None):
                                           _stream_handle(stream))
     if st != 0:
         raise KtanhError(st, "ktanh_probe_write")
+
+
+def ktanh_probe_lstm(gates: torch.Tensor, c_in: torch.Tensor, c_out: torch.Tensor, h_out: torch.Tensor,
+                     stream=None):
+    """The launch of ``klstm_cell`` with the arithmetic taken out: gates [T, B, 4H] 16-bit, c [B, H]
+    Float32, h_out [T, B, H] 16-bit."""
+    _check(gates, _BF16_VIEWS, "gates")
+    _check(h_out, _BF16_VIEWS, "h_out")
+    T, B, H4 = gates.shape
+    H = H4 // 4
+    if tuple(h_out.shape) != (T, B, H) or tuple(c_in.shape) != (B, H) or tuple(c_out.shape) != (B, H):
+        raise ValueError("shapes: gates [T, B, 4H], c_in and c_out [B, H], h_out [T, B, H]")
+    for name, t in (("c_in", c_in), ("c_out", c_out)):
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32):
+            raise ValueError(f"{name} must be a contiguous CUDA Float32 tensor")
+    st = load_library().ktanh_probe_lstm(gates.data_ptr(), c_in.data_ptr(), c_out.data_ptr(),
+                                         h_out.data_ptr(), T, B, H, _stream_handle(stream))
+    if st != 0:
+        raise KtanhError(st, "ktanh_probe_lstm")
+    return h_out

@@ -312,7 +312,8 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(gpu, oracle):
 
 def test_probe_yardsticks(gpu):
     """The measurement library: ktanh_probe_copy moves bits unchanged (NaN payloads included) for any
-    alignment and in place; ktanh_probe_write fills exactly its range; ktanh_probe_read writes nothing."""
+    alignment and in place; ktanh_probe_write fills exactly its range; ktanh_probe_read writes nothing;
+    ktanh_probe_lstm writes the XOR of the words it loads."""
     binding, torch = gpu
     from paper_1909_07729_amd import probe
     x = np.concatenate([wl.all_bf16_patterns(), wl.lstm_gate_preactivations(100003, seed=73)])
@@ -337,6 +338,22 @@ def test_probe_yardsticks(gpu):
     probe.ktanh_probe_read(buf[start:start + 30008], sink)
     torch.cuda.synchronize()
     assert np.all(_to_host(sink, np.uint16) == 0x5A5A) and np.array_equal(_to_host(buf, np.uint16), res)
+    # the LSTM kernel's launch without its arithmetic: output word = XOR of the step's four gate words and
+    # the bits of the lane's first state value; the state passes through (ragged last block, short and long T)
+    for T, B, H in ((1, 3, 8), (5, 3, 40), (8, 2, 1032), (19, 5, 264)):
+        rng = np.random.Generator(np.random.PCG64(T * 1000 + H))
+        g = rng.integers(0, 1 << 16, size=(T, B, 4 * H), dtype=np.uint16)
+        c = rng.standard_normal((B, H), dtype=np.float32)
+        gd, cd = _to_dev(torch, g), torch.from_numpy(c).to("cuda:0")
+        c_out = torch.zeros_like(cd)
+        hd = torch.full((T, B, H), 0x5A5A, dtype=torch.int16, device="cuda:0")
+        probe.ktanh_probe_lstm(gd, cd, c_out, hd)
+        words = g.reshape(T, B, 4, H // 2, 2).astype(np.uint32)
+        words = words[..., 0] | (words[..., 1] << 16)                       # [T, B, 4, H/2]
+        want = words[:, :, 0] ^ words[:, :, 1] ^ words[:, :, 2] ^ words[:, :, 3] ^ c.view(np.uint32)[None, :, 0::2]
+        got = _to_host(hd, np.uint16).reshape(T, B, H // 2, 2).astype(np.uint32)
+        assert np.array_equal(got[..., 0] | (got[..., 1] << 16), want), (T, B, H)
+        assert np.array_equal(c_out.cpu().numpy().view(np.uint32), c.view(np.uint32))
 
 
 def test_graph_replay_of_the_later_entry_points(gpu, oracle):
