@@ -333,7 +333,7 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
             binding.klstm_cell(gates[t:t + 1], c, c_out=c, h_out=h[t:t + 1])
     rec = record("klstm_cell_per_step", "gates [64,256,8192] bf16 ~ N(0,4), c [256,2048] fp32; 64 calls of one "
                  "time step each (replayed as a HIP graph), figures per call",
-                 lambda i: graph.replay(), cells * T, 18, 40, 20)
+                 lambda i: graph.replay(), cells * T, 18, 100, 200)  # 45 ms of warm-up: the clocks settle slowly under launch-bound work
     for key in ("avg_launch_us", "median_launch_us", "min_launch_us"):
         rec[key] /= T
     record("klstm_cell_fused_T64", "same shapes, 3 rotating gate/h buffers; one call carries c through all 64 steps",
