@@ -289,13 +289,19 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
                 lambda i: probe.ktanh_probe_read(x4[i % 4], sink), n4, 2, 200, 60)
     wr = record("probe_write_mlp", "ktanh_probe_write: the stores of that launch alone (2 B per element)",
                 lambda i: probe.ktanh_probe_write(y4[i % 4]), n4, 2, 200, 60)
+    rdw = record("probe_read_wide_mlp", "ktanh_probe_read_wide: the same loads from 512-thread blocks (an eighth of the blocks to dispatch)",
+                 lambda i: probe.ktanh_probe_read(x4[i % 4], sink, wide=True), n4, 2, 200, 60)
+    wrw = record("probe_write_wide_mlp", "ktanh_probe_write_wide: the same stores from 512-thread blocks",
+                 lambda i: probe.ktanh_probe_write(y4[i % 4], wide=True), n4, 2, 200, 60)
     out["size_sweep"] = run_size_sweep(torch, binding, x4, y4)
     del x4, y4
     out["memory_system"] = {
-        "note": "single-wavefront blocks are bound by the dispatcher when they only read or only write; "
-                "the read+write stream is what the library launches",
+        "note": "single-wavefront blocks are bound by the dispatcher when they only read or only write "
+                "(the read+write stream the library launches needs half the blocks per byte); 512-thread "
+                "blocks show what the memory system gives the same accesses in one direction alone",
         "copy_gb_per_s": cp["hbm_gb_per_s"], "read_only_gb_per_s": rd["hbm_gb_per_s"],
-        "write_only_gb_per_s": wr["hbm_gb_per_s"]}
+        "write_only_gb_per_s": wr["hbm_gb_per_s"], "read_only_wide_gb_per_s": rdw["hbm_gb_per_s"],
+        "write_only_wide_gb_per_s": wrw["hbm_gb_per_s"]}
 
     x3 = [upload(wl.f32_mixture())]
     x3.append(x3[0].roll(4099))
@@ -479,6 +485,10 @@ def run_probe(torch, binding, probe, wl, upload, headline):
         probe.ktanh_probe_read(x4[k % 4], sink)
     for k in range(20):
         probe.ktanh_probe_write(y4[k % 4])
+    for k in range(20):
+        probe.ktanh_probe_read(x4[k % 4], sink, wide=True)
+    for k in range(20):
+        probe.ktanh_probe_write(y4[k % 4], wide=True)
     for k in range(2):
         y4[k].copy_(x4[1 - k])                      # plain copy: 268,435,456 B each way
     torch.cuda.synchronize()

@@ -30,6 +30,12 @@ ktanh_status_t ktanh_probe_read(const void *in, void *sink, size_t n_bytes, ktan
  * out: device, 1 KiB aligned, n_bytes a multiple of 16. */
 ktanh_status_t ktanh_probe_write(void *out, size_t n_bytes, ktanh_stream_t stream);
 
+/* The same two with 512-thread blocks (eight wavefronts, one vector per lane): the launch shape of
+ * the library asks the dispatcher for one block per KiB, which bounds a launch that only reads or
+ * only writes; these show what the memory system itself gives to each direction.  Arguments as above. */
+ktanh_status_t ktanh_probe_read_wide(const void *in, void *sink, size_t n_bytes, ktanh_stream_t stream);
+ktanh_status_t ktanh_probe_write_wide(void *out, size_t n_bytes, ktanh_stream_t stream);
+
 /* The launch of klstm_cell with the arithmetic taken out: the same loads (four gate words per lane
  * and step, prefetched the same number of steps ahead), stores, waits and loop.  Output word (t, b, j)
  * of h_out, taken as 32 bits over two neighbouring cells, is the XOR of the step's four gate words

@@ -12,6 +12,7 @@ from .binding import KtanhError, _BF16_VIEWS, _check, _stream_handle
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libktanh_probe.so")
 SIGNATURES = {"ktanh_probe_copy": "ppns", "ktanh_probe_read": "ppns", "ktanh_probe_write": "pns",
+              "ktanh_probe_read_wide": "ppns", "ktanh_probe_write_wide": "pns",
               "ktanh_probe_lstm": "ppppnnns"}
 EXPORTS = tuple(SIGNATURES)
 
@@ -46,26 +47,28 @@ def ktanh_probe_copy(x, out, stream=None):
     return out
 
 
-def ktanh_probe_read(x: torch.Tensor, sink: torch.Tensor, stream=None):
-    """The loads of that launch alone over the bytes of ``x``; ``sink`` is 1 KiB of device scratch."""
+def ktanh_probe_read(x: torch.Tensor, sink: torch.Tensor, stream=None, wide=False):
+    """The loads of that launch alone over the bytes of ``x``; ``sink`` is 1 KiB of device scratch.
+    ``wide``: 512-thread blocks instead of the library's 64."""
     if not (x.is_cuda and sink.is_cuda and x.is_contiguous() and sink.is_contiguous()):
         raise ValueError("x and sink must be contiguous CUDA tensors")
     if sink.numel() * sink.element_size() < 1024:
         raise ValueError("sink must hold 1 KiB")
-    st = load_library().ktanh_probe_read(x.data_ptr(), sink.data_ptr(), x.numel() * x.element_size(),
-                                         _stream_handle(stream))
+    name = "ktanh_probe_read_wide" if wide else "ktanh_probe_read"
+    st = getattr(load_library(), name)(x.data_ptr(), sink.data_ptr(), x.numel() * x.element_size(),
+                                       _stream_handle(stream))
     if st != 0:
-        raise KtanhError(st, "ktanh_probe_read")
+        raise KtanhError(st, name)
 
 
-def ktanh_probe_write(out: torch.Tensor, stream=None):
-    """The stores of that launch alone over the bytes of ``out``."""
+def ktanh_probe_write(out: torch.Tensor, stream=None, wide=False):
+    """The stores of that launch alone over the bytes of ``out``.  ``wide``: 512-thread blocks."""
     if not (out.is_cuda and out.is_contiguous()):
         raise ValueError("out must be a contiguous CUDA tensor")
-    st = load_library().ktanh_probe_write(out.data_ptr(), out.numel() * out.element_size(),
-                                          _stream_handle(stream))
+    name = "ktanh_probe_write_wide" if wide else "ktanh_probe_write"
+    st = getattr(load_library(), name)(out.data_ptr(), out.numel() * out.element_size(), _stream_handle(stream))
     if st != 0:
-        raise KtanhError(st, "ktanh_probe_write")
+        raise KtanhError(st, name)
 
 
 def ktanh_probe_lstm(gates: torch.Tensor, c_in: torch.Tensor, c_out: torch.Tensor, h_out: torch.Tensor,

@@ -299,6 +299,10 @@ def test_probe_library_rejects_bad_arguments(probe):
     assert lib.ktanh_probe_read(ctypes.c_void_p(0x1010), fake, 1024, null) == 2 and lib.ktanh_probe_read(aligned, fake, 1000, null) == 4
     assert lib.ktanh_probe_write(null, 1024, null) == 1 and lib.ktanh_probe_write(ctypes.c_void_p(0x1010), 1024, null) == 2
     assert lib.ktanh_probe_write(aligned, 1 << 37, null) == 4 and lib.ktanh_probe_write(null, 0, null) == 0
+    assert lib.ktanh_probe_read_wide(null, fake, 1024, null) == 1 and lib.ktanh_probe_read_wide(aligned, fake, 1000, null) == 4
+    assert lib.ktanh_probe_read_wide(ctypes.c_void_p(0x1010), fake, 1024, null) == 2 and lib.ktanh_probe_read_wide(aligned, null, 1024, null) == 1
+    assert lib.ktanh_probe_write_wide(null, 1024, null) == 1 and lib.ktanh_probe_write_wide(ctypes.c_void_p(0x1010), 1024, null) == 2
+    assert lib.ktanh_probe_write_wide(aligned, 1 << 37, null) == 4 and lib.ktanh_probe_write_wide(null, 0, null) == 0
     cell = lib.ktanh_probe_lstm
     assert cell(null, null, null, null, 0, 4, 8, null) == 0 and cell(fake, fake, null, fake, 1, 4, 8, null) == 1
     assert cell(fake, fake, fake, fake, 1, 4, 12, null) == 4 and cell(ctypes.c_void_p(0x1002), fake, fake, fake, 1, 4, 8, null) == 2

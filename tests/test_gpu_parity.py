@@ -338,6 +338,14 @@ def test_probe_yardsticks(gpu):
     probe.ktanh_probe_read(buf[start:start + 30008], sink)
     torch.cuda.synchronize()
     assert np.all(_to_host(sink, np.uint16) == 0x5A5A) and np.array_equal(_to_host(buf, np.uint16), res)
+    # the 512-thread forms: a length that ends inside a block of eight tiles
+    buf.fill_(0x5A5A)
+    probe.ktanh_probe_write(buf[start:start + 30008], wide=True)
+    res = _to_host(buf, np.uint16)
+    assert np.all(res[start:start + 30008] == 0x3F80) and np.all(res[:start] == 0x5A5A) and np.all(res[start + 30008:] == 0x5A5A)
+    probe.ktanh_probe_read(buf[start:start + 30008], sink, wide=True)
+    torch.cuda.synchronize()
+    assert np.all(_to_host(sink, np.uint16) == 0x5A5A) and np.array_equal(_to_host(buf, np.uint16), res)
     # the LSTM kernel's launch without its arithmetic: output word = XOR of the step's four gate words and
     # the bits of the lane's first state value; the state passes through (ragged last block, short and long T)
     for T, B, H in ((1, 3, 8), (5, 3, 40), (8, 2, 1032), (19, 5, 264)):
