@@ -9,8 +9,10 @@ tensor, input already in HBM.  The tensor (105 MB of traffic) would fit the 256 
 so the steps rotate through 8 distinct input/output pairs (839 MB): what is timed is HBM, not cache.
 
 Timing: W untimed steps, a synchronisation, then exactly K steps between two readings of the host
-clock (and two HIP events on the launching stream), and a synchronisation: `value` and `ms_per_step`
-come from the host clock.  `roofline` is for the kernel behind the call: algorithmic bytes (4 B per
+clock, and a synchronisation: `value` and `ms_per_step` come from the host clock, and nothing else is
+inside that region (the same K steps are then repeated between two HIP events on the launching stream
+for `timed_region_launch_us`; recorded inside the timed region, the two events would cost a 20-step
+run 7 % of its `value`).  `roofline` is for the kernel behind the call: algorithmic bytes (4 B per
 element) over its average duration, taken with HIP events around K launches issued right behind W
 others, so that the queue never runs empty -- five such groups of max(K, 200) launches, with their
 mean, median and minimum (the timed region itself starts on an idle queue and holds the host's launch
@@ -72,23 +74,28 @@ GROUP_MIN_LAUNCHES = 200        # the two events of a group cost 4-8 us: too muc
 
 def time_steps(torch, launch, steps, warmup, groups=GROUPS, group_min=1):
     """The timed region: `warmup` untimed calls of launch(i), a synchronisation, `steps` calls between
-    two events and two readings of the host clock, a synchronisation.  Then, for the duration of the
-    kernel itself, `groups` times: `warmup` calls followed, with the queue still full, by
-    max(`steps`, `group_min`) calls between two events -- without the host's launch latency after an
-    idle queue, which the timed region holds once.  The groups follow each other with no
-    synchronisation in between.  Returns (host seconds of the timed region, event seconds per launch
-    in the timed region, [event seconds per launch of each group])."""
+    two readings of the host clock, a synchronisation -- and nothing else (an event recorded inside it
+    costs more than a microsecond per step of a 20-step region).  The same region once more between
+    two events, for the duration as the device saw it.  Then, for the duration of the kernel itself,
+    `groups` times: `warmup` calls followed, with the queue still full, by max(`steps`, `group_min`)
+    calls between two events -- without the host's launch latency after an idle queue, which a region
+    holds once.  The groups follow each other with no synchronisation in between.  Returns (host
+    seconds of the timed region, event seconds per launch of the repeated region, [event seconds per
+    launch of each group])."""
     for i in range(warmup):
         launch(i)
-    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for i in range(steps):
+        launch(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     first.record()
     for i in range(steps):
         launch(i)
     last.record()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
     region = first.elapsed_time(last) * 1e-3 / steps
     per_group = max(steps, group_min)
     marks = []
