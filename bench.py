@@ -347,11 +347,27 @@ def run_extras(torch, binding, probe, wl, upload, xs, ys):
     rec = record("klstm_cell_per_step", "gates [64,256,8192] bf16 ~ N(0,4), c [256,2048] fp32; 64 calls of one "
                  "time step each (replayed as a HIP graph), figures per call",
                  lambda i: graph.replay(), cells * T, 18, 100, 200)  # 45 ms of warm-up: the clocks settle slowly under launch-bound work
-    for key in ("avg_launch_us", "median_launch_us", "min_launch_us"):
+    for key in ("avg_launch_us", "median_launch_us", "min_launch_us", "timed_region_launch_us"):
         rec[key] /= T
     record("klstm_cell_fused_T64", "same shapes, 3 rotating gate/h buffers; one call carries c through all 64 steps",
            lambda i: binding.klstm_cell(gates_rot[i % 3], c0, c_out=c, h_out=h_rot[i % 3]), cells * T,
            10 + 8.0 / T, 400, 200)  # long enough for the clocks to settle after the launch-bound graph replays
+    # one step backwards per call, the way back-propagation through time issues it (each step's dh needs
+    # the recurrent product of the step after it, so the steps cannot share a launch); again as a graph
+    dh = h_rot[1][0]
+    dgates = torch.empty_like(gates)
+    dc_a, dc_b = torch.ones_like(c0), torch.empty_like(c0)
+    torch.cuda.synchronize()
+    graph_b = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph_b):
+        for t in range(T - 1, -1, -1):
+            binding.klstm_cell_backward(gates[t], c0, dh, dc_a, dgates=dgates[t], dc_prev=dc_b)
+            dc_a, dc_b = dc_b, dc_a
+    rec = record("klstm_cell_backward_per_step", "one LSTM-cell step backwards per call on [256,2048] cells (gates, c_prev, dh, dc_next in; "
+                 "dgates, dc_prev out: 30 B per cell), 64 calls replayed as a HIP graph, figures per call",
+                 lambda i: graph_b.replay(), cells * T, 30, 100, 200)
+    for key in ("avg_launch_us", "median_launch_us", "min_launch_us", "timed_region_launch_us"):
+        rec[key] /= T
     # the launch of the fused kernel with its arithmetic taken out, on the same buffers
     record("probe_lstm_T64", "ktanh_probe_lstm: the loads, stores, waits and loop of klstm_cell_fused_T64 with no arithmetic, same buffers",
            lambda i: probe.ktanh_probe_lstm(gates_rot[i % 3], c0, c, h_rot[i % 3]), cells * T, 10 + 8.0 / T, 400, 200)
