@@ -983,6 +983,52 @@ def test_autograd_functions_chain_the_gradient_entry_points(gpu, oracle):
         kt.ktanh(bf16_leaf(x), lut=binding.ktanh_default_lut(), intervals=64)
 
 
+# ------------------------------------------------------------------ random LSTM shapes
+def test_lstm_random_shapes_and_special_values(gpu, oracle):
+    """60 seeded draws of (T, B, H) -- every start-up and last-steps length of the kernel, ragged last
+    blocks -- with infinities, NaNs, zeros and threshold values sprinkled into gates and state: fused
+    and one call per step, 32- and 64-interval tables, and one step backwards, against the oracle."""
+    binding, torch = gpu
+    rng = np.random.Generator(np.random.PCG64(97))
+    special = np.array([0x7F80, 0xFF80, 0x7FC0, 0xFFC1, 0x7F7F, 0x0000, 0x8000, 0x0001, 0x4080, 0xC080, 0x3E80, 0x3E7F],
+                       dtype=np.uint16)
+
+    def same(c_got, h_got, c_ref, h_ref, what):
+        cn = np.isnan(c_ref)
+        assert np.array_equal(np.isnan(c_got), cn), what
+        assert np.array_equal(c_got.view(np.uint32)[~cn], c_ref.view(np.uint32)[~cn]), what
+        _assert_bf16_equal(h_got.ravel(), h_ref.ravel(), False, what)
+
+    for trial in range(60):
+        T, B, H = int(rng.integers(1, 23)), int(rng.integers(1, 8)), 8 * int(rng.integers(1, 70))
+        gates = wl.f32_to_bf16_bits(rng.standard_normal((T, B, 4 * H), dtype=np.float32) * 2)
+        c0 = rng.standard_normal((B, H), dtype=np.float32)
+        if trial % 3 == 0:
+            k = int(rng.integers(1, 6))
+            gates.reshape(-1)[rng.integers(0, gates.size, size=k)] = special[rng.integers(0, special.size, size=k)]
+        if trial % 7 == 0:
+            c0.reshape(-1)[int(rng.integers(0, c0.size))] = [np.inf, -np.inf, np.nan, 3e38][trial % 4]
+        what = f"trial {trial} T={T} B={B} H={H}"
+        gd, cd = _to_dev(torch, gates), torch.from_numpy(c0).to("cuda:0")
+        with np.errstate(all="ignore"):
+            for fn, ref in ((binding.klstm_cell, oracle.klstm_cell), (binding.klstm_cell64, oracle.klstm_cell64)):
+                c_ref, h_ref = ref(gates, c0)
+                c1, h1 = fn(gd, cd)
+                same(c1.cpu().numpy(), _to_host(h1, np.uint16), c_ref, h_ref, f"{what} fused {fn.__name__}")
+                cc, hs = cd.clone(), []
+                for t in range(T):
+                    cc, h = fn(gd[t:t + 1], cc, c_out=cc)
+                    hs.append(h)
+                same(cc.cpu().numpy(), _to_host(torch.cat(hs), np.uint16), c_ref, h_ref, f"{what} per step {fn.__name__}")
+            dh = wl.f32_to_bf16_bits(rng.standard_normal((B, H), dtype=np.float32))
+            dc = rng.standard_normal((B, H), dtype=np.float32)
+            for fn, ref in ((binding.klstm_cell_backward, oracle.klstm_cell_backward),
+                            (binding.klstm_cell64_backward, oracle.klstm_cell64_backward)):
+                dg_ref, dcp_ref = ref(gates[0], c0, dh, dc)
+                dg, dcp = fn(gd[0], cd, _to_dev(torch, dh), torch.from_numpy(dc).to("cuda:0"))
+                same(dcp.cpu().numpy(), _to_host(dg, np.uint16), dcp_ref, dg_ref, f"{what} backward {fn.__name__}")
+
+
 # ------------------------------------------------------------------ random sizes and alignments
 def test_random_sizes_and_alignments_over_every_elementwise_entry_point(gpu, oracle):
     """400 seeded draws of (entry point, n, offset of each tensor): the peeled heads and tails, the
