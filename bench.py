@@ -18,7 +18,8 @@ others, so that the queue never runs empty -- five such groups of max(K, 200) la
 mean, median and minimum (the timed region itself starts on an idle queue and holds the host's launch
 latency once, which is 2 % of a 20-step run, and the two events of a group cost 4-8 us, which is as
 much; the timed region's own event figure is reported as `timed_region_launch_us`).  An event between
-every two launches is not used: it costs 3.8 us per launch on this runtime.  `extra` holds the same figures for the other entry points on their own
+every two launches is not used for that: it costs microseconds per launch on this runtime (the run
+records what it reads and what it costs as `roofline.one_event_pair_per_launch`).  `extra` holds the same figures for the other entry points on their own
 workloads, the yardsticks of the measurement library (the same launch with the arithmetic, the
 stores or the loads taken out) and a sweep over tensor sizes with its fitted fixed cost per launch.
 `cpu_baseline` times the reference oracle (plain scalar C) on every workload, on one thread and on
@@ -112,6 +113,23 @@ def time_steps(torch, launch, steps, warmup, groups=GROUPS, group_min=1):
     return wall, region, [a.elapsed_time(b) * 1e-3 / per_group for a, b in marks]
 
 
+def one_event_pair_per_launch(torch, launch, n):
+    """The other way to time a kernel: an event before and after every single launch.  On this runtime
+    each recorded event occupies the queue for microseconds, so both the pairs' own readings and the
+    pace of the run they perturb are reported, next to the undisturbed figures."""
+    pairs = []
+    for i in range(n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        launch(i)
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    us = sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+    return {"launches": n, "median_us": statistics.median(us), "min_us": us[0], "mean_us": sum(us) / n,
+            "us_per_step_of_that_run": pairs[0][0].elapsed_time(pairs[-1][1]) * 1e3 / n}
+
+
 def launch_stats(region, per_launch):
     """Microseconds per launch: mean, median and minimum over the back-to-back groups, and the figure
     of the timed region itself (which starts on an idle queue)."""
@@ -188,6 +206,7 @@ def main():
 
     wall, region, per_launch = time_steps(torch, headline, args.steps, args.warmup, group_min=GROUP_MIN_LAUNCHES)
     stats = launch_stats(region, per_launch)
+    stats["one_event_pair_per_launch"] = one_event_pair_per_launch(torch, headline, GROUP_MIN_LAUNCHES)
     ms_per_step = wall / args.steps * 1e3
     achieved = 4.0 * n / (stats["avg_launch_us"] * 1e-6) / 1e9
     result = {
