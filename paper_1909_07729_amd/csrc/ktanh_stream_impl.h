@@ -96,10 +96,16 @@ inline ktanh_status_t pack_for(const ktanh_lut64_t *lut, bool f32, KtLutPack *pa
     return f32 ? kt_pack_lut64_f32(lut, pack) : kt_pack_lut64_bf16(lut, pack);
 }
 
-// The Taylor polynomials have one fixed table; the caller's table argument is not used.
+// The Taylor polynomials have one fixed table, formed once per process; the caller's table argument
+// is not used.
 inline ktanh_status_t pack_for(const ktanh_lut_t *, bool, KtTaylorPack *pack)
 {
-    kt_pack_taylor(pack);
+    static const KtTaylorPack table = [] {
+        KtTaylorPack t;
+        kt_pack_taylor(&t);
+        return t;
+    }();
+    *pack = table;
     return KT_OK;
 }
 
